@@ -1,0 +1,213 @@
+"""fp64 reference for spectral key editing and the causal attention that reads it.
+
+TEST INFRASTRUCTURE: imported only by tests, the smoke check and the CPU-baseline
+leg of the benchmark.  Shares no code, tables or helpers with the HIP kernels.
+
+Every function takes and returns numpy float64 arrays (masks are integer arrays).
+Shapes follow the key-editing hook of the paper's Algorithms 1 and 2:
+keys are K[B, T, H, d] (batch, token, KV head, head dim) and the highlight mask
+is m[B, T], shared by all heads.  Queries are Q[B, T, Hq, d] with Hq = G * H;
+query head hq reads KV head hq // G (contiguous groups: a reading, the paper
+does not state the grouping).
+
+What is written out here, in the order the paper states it:
+
+* Eq. 2            P = U_{:, :k} U_{:, :k}^T                      -> projector
+* Sec. 3.3         P_dynamic = sum_m alpha_m U_m U_m^T            -> blended_projector
+* Sec. 2 / Alg. 2  k' = k + g * P k on highlighted tokens only    -> edit_keys
+* Sec. 2           Attn(i, j) = q_i . k_j / sqrt(d_k), causal softmax, weighted sum of V
+                                                                  -> causal_attention
+* Eq. 6            alpha_m = sum_k (q.u_m^(k)) sigma_m^(k) / max_m |.|   -> route_eq6
+* benchmark's routing rule  w = softmax_m(tau * cos(mean prompt query, prototype_m))
+                                                                  -> route_softmax_cos
+
+Pins (tests/test_oracle_*.py): closed form of Appendix C, score-side form of
+Eq. 5, query-side form (Sec. 2), library scaled-dot-product attention, and
+brute-force scalar loops on tiny shapes.  No function here is unpinned.
+"""
+import numpy as np
+
+_F = np.float64
+
+
+def projector(U):
+    """Eq. 2: orthogonal projector onto the span of the orthonormal columns of U[d, r]."""
+    U = np.asarray(U, dtype=_F)
+    return U @ U.T
+
+
+def blended_projector(U_bank, alpha):
+    """Sec. 3.3: P_dynamic = sum_m alpha_m * U_m U_m^T for one (layer, KV head).
+
+    U_bank[M, d, r] holds the retained columns of every expert, alpha[M] the
+    routing coefficients.  SEKA is the case M = 1, alpha = 1 (Appendix D).
+    """
+    U_bank = np.asarray(U_bank, dtype=_F)
+    alpha = np.asarray(alpha, dtype=_F)
+    d = U_bank.shape[1]
+    P = np.zeros((d, d), dtype=_F)
+    for m in range(U_bank.shape[0]):
+        P += alpha[m] * projector(U_bank[m])
+    return P
+
+
+def edit_keys(K, U, gain, mask, w=None):
+    """Hook of Algorithms 1/2: K[b,t,h,:] += g_h * P_{b,h} K[b,t,h,:] where m[b,t] != 0.
+
+    K[B,T,H,d]; U[H,M,d,r]; gain[H] (0 = head not selected, Sec. 3.4);
+    mask[B,T]; w[B,H,M] routing coefficients or None for all-ones (SEKA).
+    Returns a new array; rows that are not highlighted are copied untouched.
+    """
+    K = np.asarray(K, dtype=_F)
+    U = np.asarray(U, dtype=_F)
+    B, T, H, d = K.shape
+    M = U.shape[1]
+    K_out = K.copy()
+    for b in range(B):
+        hl = np.flatnonzero(np.asarray(mask[b]) != 0)
+        if hl.size == 0:
+            continue
+        for h in range(H):
+            g = float(gain[h])
+            if g == 0.0:
+                continue
+            alpha = np.ones(M, dtype=_F) if w is None else np.asarray(w[b, h], dtype=_F)
+            P = blended_projector(U[h], alpha)
+            k = K[b, hl, h, :]                      # [n, d], one key per row
+            delta = g * (k @ P.T)                   # row form of g * P k
+            K_out[b, hl, h, :] = k + delta
+    return K_out
+
+
+def causal_attention(Q, K, V, scale=None):
+    """Sec. 2: scores q_i.k_j / sqrt(d_k) for j <= i, softmax over j, weighted sum of V.
+
+    Materialises the full T x T score matrix per (batch, query head).
+    Returns O[B,T,Hq,d] and LSE[B,Hq,T] (log of the softmax denominator,
+    including the subtracted row maximum).
+    """
+    Q = np.asarray(Q, dtype=_F)
+    K = np.asarray(K, dtype=_F)
+    V = np.asarray(V, dtype=_F)
+    B, T, Hq, d = Q.shape
+    H = K.shape[2]
+    G = Hq // H
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    O = np.empty_like(Q)
+    LSE = np.empty((B, Hq, T), dtype=_F)
+    visible = np.tril(np.ones((T, T), dtype=bool))
+    for b in range(B):
+        for hq in range(Hq):
+            h = hq // G
+            A = scale * (Q[b, :, hq, :] @ K[b, :, h, :].T)       # [T, T]
+            A = np.where(visible, A, -np.inf)
+            row_max = A.max(axis=1, keepdims=True)
+            E = np.exp(A - row_max)
+            denom = E.sum(axis=1, keepdims=True)
+            O[b, :, hq, :] = (E / denom) @ V[b, :, h, :]
+            LSE[b, hq, :] = (row_max + np.log(denom))[:, 0]
+    return O, LSE
+
+
+def steered_attention(Q, K, V, U, gain, mask, w=None, scale=None):
+    """Edited keys first (materialised), then ordinary causal attention on them."""
+    K_edit = edit_keys(K, U, gain, mask, w)
+    return causal_attention(Q, K_edit, V, scale)
+
+
+def attention_rows(Q, K, V, rows, scale=None):
+    """The same attention for a list of (b, hq, i) output rows, one at a time.
+
+    K is whatever the queries should see (already edited if steering is on).
+    Each row only needs keys and values 0..i, so this is how outputs are
+    checked at sizes where the full score matrix is too large for the host.
+    Returns O_rows[n, d] and LSE_rows[n].
+    """
+    B, T, Hq, d = Q.shape
+    H = K.shape[2]
+    G = Hq // H
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    out = np.empty((len(rows), d), dtype=_F)
+    lse = np.empty(len(rows), dtype=_F)
+    for n, (b, hq, i) in enumerate(rows):
+        h = hq // G
+        q = np.asarray(Q[b, i, hq, :], dtype=_F)
+        k = np.asarray(K[b, : i + 1, h, :], dtype=_F)
+        v = np.asarray(V[b, : i + 1, h, :], dtype=_F)
+        a = scale * (k @ q)
+        a_max = a.max()
+        e = np.exp(a - a_max)
+        s = e.sum()
+        out[n] = (e / s) @ v
+        lse[n] = a_max + np.log(s)
+    return out, lse
+
+
+def mean_group_query(Q, H, t0, t1):
+    """Mean of the queries of tokens [t0, t1) over the G query heads of each KV head.
+
+    Q[B,T,Hq,d] -> q_bar[B,H,d].  [t0, t1) = [T-1, T) is the paper's last-token
+    query (Sec. 3.3); [0, T) is the benchmark's mean prompt query.
+    """
+    Q = np.asarray(Q, dtype=_F)
+    B, T, Hq, d = Q.shape
+    G = Hq // H
+    q_bar = np.empty((B, H, d), dtype=_F)
+    for b in range(B):
+        for h in range(H):
+            q_bar[b, h] = Q[b, t0:t1, h * G:(h + 1) * G, :].reshape(-1, d).mean(axis=0)
+    return q_bar
+
+
+def route_softmax_cos(Q, proto, t0, t1, tau):
+    """Benchmark routing rule: w = softmax_m(tau * cos(q_bar, prototype_m)).
+
+    proto[H,M,d].  A zero-length q_bar or prototype gives cos = 0 for that
+    expert (so all-zero queries give uniform weights).  Returns w[B,H,M].
+    """
+    proto = np.asarray(proto, dtype=_F)
+    H, M, d = proto.shape
+    q_bar = mean_group_query(Q, H, t0, t1)
+    B = q_bar.shape[0]
+    w = np.empty((B, H, M), dtype=_F)
+    for b in range(B):
+        for h in range(H):
+            cos = np.zeros(M, dtype=_F)
+            qn = np.sqrt(q_bar[b, h] @ q_bar[b, h])
+            for m in range(M):
+                pn = np.sqrt(proto[h, m] @ proto[h, m])
+                if qn * pn >= 1e-30:
+                    cos[m] = (q_bar[b, h] @ proto[h, m]) / (qn * pn)
+            z = tau * cos
+            e = np.exp(z - z.max())
+            w[b, h] = e / e.sum()
+    return w
+
+
+def route_eq6(Q, U_top, sigma, t0, t1):
+    """Eq. 6: alpha_m = sum_{k<=K} (q.u_m^(k)) sigma_m^(k) / max_m' |sum_k ...|.
+
+    U_top[H,M,d,K] are the top-K left singular vectors of every expert,
+    sigma[H,M,K] their singular values.  q is the query of tokens [t0, t1)
+    averaged over the query heads of the group (the paper uses the last
+    token, [T-1, T)).  If every alignment is below 1e-30 in magnitude the
+    coefficients are 0 (no steering).  Returns alpha[B,H,M].
+    """
+    U_top = np.asarray(U_top, dtype=_F)
+    sigma = np.asarray(sigma, dtype=_F)
+    H, M, d, Ktop = U_top.shape
+    q_bar = mean_group_query(Q, H, t0, t1)
+    B = q_bar.shape[0]
+    alpha = np.zeros((B, H, M), dtype=_F)
+    for b in range(B):
+        for h in range(H):
+            a = np.zeros(M, dtype=_F)
+            for m in range(M):
+                for k in range(Ktop):
+                    a[m] += (q_bar[b, h] @ U_top[h, m, :, k]) * sigma[h, m, k]
+            biggest = np.abs(a).max()
+            if biggest >= 1e-30:
+                alpha[b, h] = a / biggest
+    return alpha

@@ -1,0 +1,139 @@
+/*
+ * seka.h — C ABI of the MI355X (gfx950) SEKA / AdaSEKA prefill library.
+ *
+ * The library computes causal grouped-query prefill attention whose keys are spectrally
+ * edited before scoring (paper Sec. 2: k'_j = k_j + g P k_j on highlighted tokens j, one
+ * projector P per (layer, KV head); Sec. 3.3: for AdaSEKA P = sum_m alpha_m U_m U_m^T).
+ *
+ * General conventions (all entry points):
+ *   - Tensors are row-major [B, S, H, D] (batch, token, head, head dim; the layout of the
+ *     key-editing hook's input in Algorithms 1 and 2), D contiguous.  Query head hq reads
+ *     KV head hq / (Hq / Hkv).
+ *   - "dev" pointers are device (HBM) addresses on the current HIP device, owned by the caller,
+ *     16-byte aligned.  "host" pointers are ordinary host memory, read before the call returns.
+ *   - Calls validate their arguments on the host first (no GPU work is issued on error), then
+ *     enqueue kernels on `hip_stream` (a hipStream_t passed as void*; NULL = the default
+ *     stream) and return without waiting.  The library never allocates or frees device memory.
+ *   - Inputs are never written.  Outputs must not overlap inputs unless stated.
+ *   - Return value: SEKA_OK or an error code; seka_status_string() names it.
+ */
+#ifndef SEKA_H
+#define SEKA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SEKA_OK = 0,
+  SEKA_ERR_NULL = 1,        /* a required pointer is NULL                                  */
+  SEKA_ERR_SHAPE = 2,       /* a dimension is out of range or inconsistent                 */
+  SEKA_ERR_DTYPE = 3,       /* unknown element type                                        */
+  SEKA_ERR_ALIGN = 4,       /* a device pointer is not 16-byte aligned                     */
+  SEKA_ERR_ALIAS = 5,       /* an output overlaps an input in a way that is not allowed    */
+  SEKA_ERR_UNSUPPORTED = 6, /* valid request that this build has no kernel for             */
+  SEKA_ERR_LAUNCH = 7,      /* the HIP runtime reported an error on launch                 */
+  SEKA_ERR_WORKSPACE = 8    /* workspace missing or too small                              */
+} seka_status;
+
+typedef enum { SEKA_F32 = 0, SEKA_BF16 = 1 } seka_dtype;
+
+typedef enum {
+  SEKA_ROUTE_SOFTMAX_COS = 0, /* w = softmax_m(tau * cos(q_bar, prototype_m))                */
+  SEKA_ROUTE_PAPER_EQ6 = 1    /* alpha_m = <q_bar, p_m> / max_m' |<q_bar, p_m'>|  (Eq. 6)    */
+} seka_route_mode;
+
+enum { SEKA_MAX_RANK = 128, SEKA_MAX_KV_HEADS = 64, SEKA_MAX_EXPERTS = 16 };
+
+/* Problem shape.  D must be 64 or 128; Hq must be a multiple of Hkv; Hkv <= SEKA_MAX_KV_HEADS. */
+typedef struct {
+  int32_t B, S, Hq, Hkv, D;
+  int32_t dtype;          /* seka_dtype: element type of Q, K, V, O and U                      */
+  float softmax_scale;    /* scores are scale * q.k; <= 0 selects 1/sqrt(D) (paper Sec. 2)     */
+} seka_shape;
+
+/* Steering of one layer (paper Algorithm 1 hook inputs; Algorithm 2 for M > 1). */
+typedef struct {
+  int32_t M;              /* experts per KV head; 1 = SEKA                                     */
+  int32_t r;              /* retained columns per expert; M*r <= SEKA_MAX_RANK; for bf16 tensors
+                             r must be a multiple of 8 (pad U with zero columns otherwise)     */
+  const void* U;          /* dev [Hkv, M, D, r], tensor dtype: column c of U[h,m] is the c-th
+                             basis vector of expert m's subspace (Eq. 2: P = U U^T)            */
+  const float* w;         /* dev [B, Hkv, M] fp32 routing coefficients (output of seka_route),
+                             or NULL for all ones (SEKA)                                       */
+  const float* gain;      /* host [Hkv] fp32: g of k' = k + g P k; any real value; 0 means the
+                             head is not selected for steering (paper Sec. 3.4)                */
+  const uint8_t* mask;    /* dev [B, S]: nonzero = highlighted token (Algorithm 1, "if m_{b,t}
+                             = 1"); shared by all heads                                        */
+} seka_steer;
+
+/*
+ * seka_route — AdaSEKA expert coefficients from the prompt's queries (paper Sec. 3.3, Eq. 6).
+ *
+ * q_bar[b,h,:] = mean of Q[b, t, hq, :] over tokens t in [t0, t1) and over the Hq/Hkv query
+ * heads hq of KV head h.  Then per (b, h):
+ *   SOFTMAX_COS: w_m = softmax_m(tau * <q_bar, p_m> / (|q_bar| |p_m|)); a product of norms
+ *                below 1e-30 gives cos = 0.
+ *   PAPER_EQ6:   alpha_m = <q_bar, p_m> / max_m' |<q_bar, p_m'>| with p_m = sum_k sigma_m^(k)
+ *                u_m^(k) precomputed by the caller (the K-term sum of Eq. 6 is linear in q);
+ *                all-zero alignments (max < 1e-30) give alpha = 0.  The paper uses the last
+ *                prompt token: [t0, t1) = [S-1, S).  tau is ignored.
+ *
+ * Q      dev [B,S,Hq,D] tensor dtype.          proto  dev [Hkv,M,D] fp32.
+ * w_out  dev [B,Hkv,M] fp32 (written).         1 <= M <= SEKA_MAX_EXPERTS, 0 <= t0 < t1 <= S.
+ * workspace  dev scratch of at least seka_route_workspace_bytes(sh, t0, t1) bytes, 16-byte
+ *            aligned; contents on return are unspecified.  Calls sharing a workspace must be
+ *            ordered by their stream.
+ */
+size_t seka_route_workspace_bytes(const seka_shape* sh, int32_t t0, int32_t t1);
+seka_status seka_route(const void* Q, const seka_shape* sh, const float* proto, int32_t M,
+                       int32_t t0, int32_t t1, int32_t mode, float tau, float* w_out,
+                       void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * seka_edit_keys — the standalone key-editing hook (Algorithm 1 / 2, inference part):
+ *   K_out[b,t,h,:] = K_in[b,t,h,:] + gain[h] * sum_m w[b,h,m] U[h,m] (U[h,m]^T K_in[b,t,h,:])
+ * where mask[b,t] != 0 and gain[h] != 0; K_out = K_in elsewhere.
+ *
+ * K_in, K_out  dev [B,S,Hkv,D] tensor dtype.  K_out == K_in is allowed (then only highlighted
+ * rows of selected heads are written); any other overlap returns SEKA_ERR_ALIAS.
+ * sh->Hq is ignored.  Accumulation is fp32; the result is rounded once to the tensor dtype.
+ */
+seka_status seka_edit_keys(const void* K_in, void* K_out, const seka_shape* sh,
+                           const seka_steer* st, void* hip_stream);
+
+/*
+ * seka_attention_prefill — causal attention on the edited keys, edit fused in (paper Sec. 2 and
+ * Eq. 5: logits_ij = q_i . k'_j / sqrt(d_k), j <= i; softmax over j; O_i = sum_j p_ij v_j).
+ * K itself is not modified: edited keys exist only on chip.
+ *
+ * Q, O  dev [B,S,Hq,D];  K, V  dev [B,S,Hkv,D];  all tensor dtype.
+ * lse   dev [B,Hq,S] fp32 or NULL: natural log of the softmax denominator (row maximum included).
+ * st == NULL, st->mask == NULL or all gains zero gives exactly seka_attention_plain.
+ * bf16 tensors: products on the matrix cores with fp32 accumulation, softmax in fp32.
+ */
+seka_status seka_attention_prefill(const void* Q, const void* K, const void* V, void* O,
+                                   float* lse, const seka_shape* sh, const seka_steer* st,
+                                   void* hip_stream);
+
+/* seka_attention_plain — the same attention with unedited keys (the unsteered baseline). */
+seka_status seka_attention_plain(const void* Q, const void* K, const void* V, void* O, float* lse,
+                                 const seka_shape* sh, void* hip_stream);
+
+/* Name of a status code; static storage, never NULL. */
+const char* seka_status_string(int32_t status);
+
+/*
+ * seka_set_tuning — select among kernel variants that compute the same result (for benchmarks).
+ * key 0: bf16 attention variant id (0 = library default).  Unknown keys/values return
+ * SEKA_ERR_UNSUPPORTED and change nothing.  Not thread-safe with concurrent launches.
+ */
+seka_status seka_set_tuning(int32_t key, int32_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SEKA_H */

@@ -1,0 +1,158 @@
+"""ctypes binding of libseka (the C ABI declared in include/seka.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.
+PyTorch tensors are used as device buffers (data_ptr) and for the current HIP stream.
+Importing this module raises if the shared library has not been built
+(`python -m paper_2603_01281_amd.build`); there is no CPU fallback.
+"""
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libseka.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2603_01281_amd.build`")
+
+lib = ctypes.CDLL(LIB_PATH)
+
+SEKA_OK = 0
+SEKA_F32, SEKA_BF16 = 0, 1
+SEKA_ROUTE_SOFTMAX_COS, SEKA_ROUTE_PAPER_EQ6 = 0, 1
+SEKA_MAX_RANK, SEKA_MAX_KV_HEADS, SEKA_MAX_EXPERTS = 128, 64, 16
+
+
+class seka_shape(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("S", ctypes.c_int32), ("Hq", ctypes.c_int32), ("Hkv", ctypes.c_int32),
+                ("D", ctypes.c_int32), ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float)]
+
+
+class seka_steer(ctypes.Structure):
+    _fields_ = [("M", ctypes.c_int32), ("r", ctypes.c_int32), ("U", ctypes.c_void_p), ("w", ctypes.c_void_p),
+                ("gain", ctypes.POINTER(ctypes.c_float)), ("mask", ctypes.c_void_p)]
+
+
+_vp, _i32, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+_shape_p, _steer_p = ctypes.POINTER(seka_shape), ctypes.POINTER(seka_steer)
+
+lib.seka_status_string.restype = ctypes.c_char_p
+lib.seka_status_string.argtypes = [_i32]
+lib.seka_set_tuning.restype = _i32
+lib.seka_set_tuning.argtypes = [_i32, _i32]
+lib.seka_route_workspace_bytes.restype = _sz
+lib.seka_route_workspace_bytes.argtypes = [_shape_p, _i32, _i32]
+lib.seka_route.restype = _i32
+lib.seka_route.argtypes = [_vp, _shape_p, _vp, _i32, _i32, _i32, _i32, _f32, _vp, _vp, _sz, _vp]
+lib.seka_edit_keys.restype = _i32
+lib.seka_edit_keys.argtypes = [_vp, _vp, _shape_p, _steer_p, _vp]
+lib.seka_attention_prefill.restype = _i32
+lib.seka_attention_prefill.argtypes = [_vp, _vp, _vp, _vp, _vp, _shape_p, _steer_p, _vp]
+lib.seka_attention_plain.restype = _i32
+lib.seka_attention_plain.argtypes = [_vp, _vp, _vp, _vp, _vp, _shape_p, _vp]
+
+
+class SekaError(RuntimeError):
+    def __init__(self, status):
+        self.status = status
+        super().__init__(f"seka status {status}: {lib.seka_status_string(status).decode()}")
+
+
+def _check(status):
+    if status != SEKA_OK:
+        raise SekaError(status)
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def _dtype_code(t):
+    torch = _torch()
+    if t.dtype == torch.float32:
+        return SEKA_F32
+    if t.dtype == torch.bfloat16:
+        return SEKA_BF16
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _dev(t, name):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous tensor in device memory")
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        return _torch().cuda.current_stream().cuda_stream
+    return stream
+
+
+def _shape(B, S, Hq, Hkv, D, dtype, scale):
+    return seka_shape(B, S, Hq, Hkv, D, dtype, float(scale))
+
+
+def _steer(U, gain, mask, w, Hkv):
+    """U [Hkv,M,D,r] device tensor; gain: host sequence of Hkv floats; mask [B,S] uint8 device; w [B,Hkv,M] fp32 device or None."""
+    if U.dim() != 4:
+        raise ValueError("U must be [Hkv, M, D, r]")
+    gains = (ctypes.c_float * Hkv)(*[float(g) for g in gain])
+    st = seka_steer(int(U.shape[1]), int(U.shape[3]), _dev(U, "U"), _dev(w, "w"), gains, _dev(mask, "mask"))
+    st._keepalive = gains
+    return st
+
+
+def seka_set_tuning(key, value):
+    _check(lib.seka_set_tuning(key, value))
+
+
+def seka_route_workspace_bytes(B, S, Hq, Hkv, D, dtype, t0, t1):
+    sh = _shape(B, S, Hq, Hkv, D, dtype, 0.0)
+    return lib.seka_route_workspace_bytes(ctypes.byref(sh), t0, t1)
+
+
+def seka_route(Q, proto, t0, t1, mode=SEKA_ROUTE_SOFTMAX_COS, tau=10.0, w_out=None, workspace=None, stream=None):
+    """Q [B,S,Hq,D] (fp32|bf16), proto [Hkv,M,D] fp32 -> w_out [B,Hkv,M] fp32 (allocated if None)."""
+    torch = _torch()
+    B, S, Hq, D = Q.shape
+    Hkv, M, _ = proto.shape
+    sh = _shape(B, S, Hq, Hkv, D, _dtype_code(Q), 0.0)
+    if w_out is None:
+        w_out = torch.empty((B, Hkv, M), dtype=torch.float32, device=Q.device)
+    need = lib.seka_route_workspace_bytes(ctypes.byref(sh), t0, t1)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=Q.device)
+    _check(lib.seka_route(_dev(Q, "Q"), ctypes.byref(sh), _dev(proto, "proto"), M, t0, t1, mode, float(tau),
+                          _dev(w_out, "w_out"), _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
+                          _stream(stream)))
+    return w_out
+
+
+def seka_edit_keys(K_in, K_out, U, gain, mask, w=None, stream=None):
+    """K_in/K_out [B,S,Hkv,D]; K_out may be K_in itself (in place)."""
+    B, S, Hkv, D = K_in.shape
+    sh = _shape(B, S, Hkv, Hkv, D, _dtype_code(K_in), 0.0)
+    st = _steer(U, gain, mask, w, Hkv)
+    _check(lib.seka_edit_keys(_dev(K_in, "K_in"), _dev(K_out, "K_out"), ctypes.byref(sh), ctypes.byref(st), _stream(stream)))
+    return K_out
+
+
+def seka_attention_prefill(Q, K, V, O, U, gain, mask, w=None, lse=None, scale=0.0, stream=None):
+    B, S, Hq, D = Q.shape
+    Hkv = K.shape[2]
+    sh = _shape(B, S, Hq, Hkv, D, _dtype_code(Q), scale)
+    st = _steer(U, gain, mask, w, Hkv)
+    _check(lib.seka_attention_prefill(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(O, "O"), _dev(lse, "lse"),
+                                      ctypes.byref(sh), ctypes.byref(st), _stream(stream)))
+    return O
+
+
+def seka_attention_plain(Q, K, V, O, lse=None, scale=0.0, stream=None):
+    B, S, Hq, D = Q.shape
+    Hkv = K.shape[2]
+    sh = _shape(B, S, Hq, Hkv, D, _dtype_code(Q), scale)
+    _check(lib.seka_attention_plain(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(O, "O"), _dev(lse, "lse"),
+                                    ctypes.byref(sh), _stream(stream)))
+    return O

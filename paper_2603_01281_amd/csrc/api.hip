@@ -1,0 +1,168 @@
+// C ABI of libseka: host-side argument validation and dispatch to the HIP launchers.
+// Every check here runs before any GPU work is issued, so error paths need no GPU.
+#include <cmath>
+#include <cstring>
+
+#include "common.h"
+
+namespace {
+
+int g_attn_bf16_variant = 0;
+
+inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+inline size_t elem_size(int dtype) { return dtype == SEKA_BF16 ? 2 : 4; }
+
+seka_status check_shape(const seka_shape* sh, bool need_q_heads) {
+  if (!sh) return SEKA_ERR_NULL;
+  if (sh->dtype != SEKA_F32 && sh->dtype != SEKA_BF16) return SEKA_ERR_DTYPE;
+  if (sh->B < 1 || sh->S < 1 || sh->Hkv < 1 || sh->Hkv > SEKA_MAX_KV_HEADS) return SEKA_ERR_SHAPE;
+  if (sh->D != 64 && sh->D != 128) return SEKA_ERR_SHAPE;
+  if (need_q_heads && (sh->Hq < 1 || sh->Hq % sh->Hkv != 0)) return SEKA_ERR_SHAPE;
+  if (!std::isfinite(sh->softmax_scale)) return SEKA_ERR_SHAPE;
+  // 32-bit element indexing inside one (batch) slice is assumed by the kernels
+  const int64_t heads = need_q_heads ? sh->Hq : sh->Hkv;
+  if ((int64_t)sh->S * heads * sh->D >= ((int64_t)1 << 31)) return SEKA_ERR_SHAPE;
+  return SEKA_OK;
+}
+
+seka_status check_steer(const seka_steer* st, const seka_shape* sh) {
+  if (!st->U || !st->gain || !st->mask) return SEKA_ERR_NULL;
+  if (st->M < 1 || st->M > SEKA_MAX_EXPERTS || st->r < 1) return SEKA_ERR_SHAPE;
+  if ((int64_t)st->M * st->r > SEKA_MAX_RANK) return SEKA_ERR_SHAPE;
+  if (st->r > sh->D) return SEKA_ERR_SHAPE;
+  if (misaligned(st->U) || (st->w && misaligned(st->w))) return SEKA_ERR_ALIGN;
+  for (int h = 0; h < sh->Hkv; ++h)
+    if (!std::isfinite(st->gain[h])) return SEKA_ERR_SHAPE;
+  if (sh->dtype == SEKA_BF16 && st->r % 8 != 0) return SEKA_ERR_UNSUPPORTED;
+  return SEKA_OK;
+}
+
+void fill_steer(seka::SteerArgs& sa, const seka_steer* st, int Hkv) {
+  std::memset(&sa, 0, sizeof(sa));
+  sa.U = st->U;
+  sa.w = st->w;
+  sa.mask = st->mask;
+  sa.M = st->M;
+  sa.r = st->r;
+  for (int h = 0; h < Hkv; ++h) sa.gain[h] = st->gain[h];
+}
+
+bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb) {
+  const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+  return x < y + nb && y < x + na;
+}
+
+seka_status attention_common(const void* Q, const void* K, const void* V, void* O, float* lse,
+                             const seka_shape* sh, const seka_steer* st, void* hip_stream) {
+  seka_status rc = check_shape(sh, true);
+  if (rc != SEKA_OK) return rc;
+  if (!Q || !K || !V || !O) return SEKA_ERR_NULL;
+  if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || (lse && misaligned(lse)))
+    return SEKA_ERR_ALIGN;
+  const size_t es = elem_size(sh->dtype);
+  const size_t nq = (size_t)sh->B * sh->S * sh->Hq * sh->D * es;
+  const size_t nk = (size_t)sh->B * sh->S * sh->Hkv * sh->D * es;
+  if (ranges_overlap(O, nq, Q, nq) || ranges_overlap(O, nq, K, nk) || ranges_overlap(O, nq, V, nk))
+    return SEKA_ERR_ALIAS;
+
+  bool steered = false;
+  seka::SteerArgs sa;
+  if (st && st->mask) {
+    rc = check_steer(st, sh);
+    if (rc != SEKA_OK) return rc;
+    for (int h = 0; h < sh->Hkv; ++h) steered |= (st->gain[h] != 0.0f);
+    if (steered) fill_steer(sa, st, sh->Hkv);
+  }
+
+  seka::AttnArgs a;
+  a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse;
+  a.B = sh->B; a.S = sh->S; a.Hq = sh->Hq; a.Hkv = sh->Hkv; a.D = sh->D;
+  a.scale = sh->softmax_scale > 0.0f ? sh->softmax_scale : 1.0f / std::sqrt((float)sh->D);
+  hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  hipError_t e = (sh->dtype == SEKA_BF16)
+                     ? seka::launch_attention_bf16(a, steered ? &sa : nullptr, g_attn_bf16_variant, stream)
+                     : seka::launch_attention_f32(a, steered ? &sa : nullptr, stream);
+  if (e == hipErrorNotSupported) return SEKA_ERR_UNSUPPORTED;
+  return e == hipSuccess ? SEKA_OK : SEKA_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* seka_status_string(int32_t status) {
+  switch (status) {
+    case SEKA_OK: return "ok";
+    case SEKA_ERR_NULL: return "a required pointer is NULL";
+    case SEKA_ERR_SHAPE: return "a dimension or scalar argument is out of range";
+    case SEKA_ERR_DTYPE: return "unknown element type";
+    case SEKA_ERR_ALIGN: return "a device pointer is not 16-byte aligned";
+    case SEKA_ERR_ALIAS: return "an output overlaps an input";
+    case SEKA_ERR_UNSUPPORTED: return "no kernel for this request";
+    case SEKA_ERR_LAUNCH: return "HIP reported an error on launch";
+    case SEKA_ERR_WORKSPACE: return "workspace missing or too small";
+    default: return "unknown status";
+  }
+}
+
+seka_status seka_set_tuning(int32_t key, int32_t value) {
+  if (key == 0 && seka::attention_bf16_variant_ok(value)) {
+    g_attn_bf16_variant = value;
+    return SEKA_OK;
+  }
+  return SEKA_ERR_UNSUPPORTED;
+}
+
+size_t seka_route_workspace_bytes(const seka_shape* sh, int32_t t0, int32_t t1) {
+  if (check_shape(sh, true) != SEKA_OK || t0 < 0 || t1 <= t0 || t1 > sh->S) return 0;
+  return seka::route_workspace_bytes(sh->B, sh->Hkv, sh->D, t0, t1);
+}
+
+seka_status seka_route(const void* Q, const seka_shape* sh, const float* proto, int32_t M, int32_t t0,
+                       int32_t t1, int32_t mode, float tau, float* w_out, void* workspace,
+                       size_t workspace_bytes, void* hip_stream) {
+  seka_status rc = check_shape(sh, true);
+  if (rc != SEKA_OK) return rc;
+  if (!Q || !proto || !w_out) return SEKA_ERR_NULL;
+  if (M < 1 || M > SEKA_MAX_EXPERTS) return SEKA_ERR_SHAPE;
+  if (t0 < 0 || t1 <= t0 || t1 > sh->S) return SEKA_ERR_SHAPE;
+  if (mode != SEKA_ROUTE_SOFTMAX_COS && mode != SEKA_ROUTE_PAPER_EQ6) return SEKA_ERR_UNSUPPORTED;
+  if (!std::isfinite(tau)) return SEKA_ERR_SHAPE;
+  if (misaligned(Q) || misaligned(proto) || (reinterpret_cast<uintptr_t>(w_out) & 3u)) return SEKA_ERR_ALIGN;
+  const size_t need = seka::route_workspace_bytes(sh->B, sh->Hkv, sh->D, t0, t1);
+  if (!workspace || workspace_bytes < need) return SEKA_ERR_WORKSPACE;
+  if (misaligned(workspace)) return SEKA_ERR_ALIGN;
+  hipError_t e = seka::launch_route(Q, sh->B, sh->S, sh->Hq, sh->Hkv, sh->D, sh->dtype, proto, M, t0, t1, mode,
+                                    tau, w_out, workspace, reinterpret_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SEKA_OK : SEKA_ERR_LAUNCH;
+}
+
+seka_status seka_edit_keys(const void* K_in, void* K_out, const seka_shape* sh, const seka_steer* st,
+                           void* hip_stream) {
+  seka_status rc = check_shape(sh, false);
+  if (rc != SEKA_OK) return rc;
+  if (!K_in || !K_out || !st) return SEKA_ERR_NULL;
+  rc = check_steer(st, sh);
+  if (rc != SEKA_OK) return rc;
+  if (misaligned(K_in) || misaligned(K_out)) return SEKA_ERR_ALIGN;
+  const size_t nk = (size_t)sh->B * sh->S * sh->Hkv * sh->D * elem_size(sh->dtype);
+  if (K_in != K_out && ranges_overlap(K_in, nk, K_out, nk)) return SEKA_ERR_ALIAS;
+  seka::SteerArgs sa;
+  fill_steer(sa, st, sh->Hkv);
+  hipError_t e = seka::launch_edit_keys(K_in, K_out, sh->B, sh->S, sh->Hkv, sh->D, sh->dtype, sa,
+                                        reinterpret_cast<hipStream_t>(hip_stream));
+  return e == hipSuccess ? SEKA_OK : SEKA_ERR_LAUNCH;
+}
+
+seka_status seka_attention_prefill(const void* Q, const void* K, const void* V, void* O, float* lse,
+                                   const seka_shape* sh, const seka_steer* st, void* hip_stream) {
+  return attention_common(Q, K, V, O, lse, sh, st, hip_stream);
+}
+
+seka_status seka_attention_plain(const void* Q, const void* K, const void* V, void* O, float* lse,
+                                 const seka_shape* sh, void* hip_stream) {
+  return attention_common(Q, K, V, O, lse, sh, nullptr, hip_stream);
+}
+
+}  // extern "C"

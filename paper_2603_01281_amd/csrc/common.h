@@ -1,0 +1,51 @@
+// Internal declarations shared by the HIP translation units of libseka (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "seka.h"
+
+namespace seka {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+// Per-launch steering parameters passed by value (gains live in kernel arguments so that a
+// zero gain can skip work without a device-side lookup).
+struct SteerArgs {
+  const void* U;        // dev [Hkv, M, D, r]
+  const float* w;       // dev [B, Hkv, M] or nullptr
+  const uint8_t* mask;  // dev [B, S]
+  int M, r;
+  float gain[SEKA_MAX_KV_HEADS];
+};
+
+struct AttnArgs {
+  const void* Q;
+  const void* K;
+  const void* V;
+  void* O;
+  float* lse;  // may be nullptr
+  int B, S, Hq, Hkv, D;
+  float scale;
+};
+
+// Launchers (defined one per .hip file).  `steer` may be nullptr for plain attention.
+hipError_t launch_attention_f32(const AttnArgs& a, const SteerArgs* steer, hipStream_t s);
+hipError_t launch_attention_bf16(const AttnArgs& a, const SteerArgs* steer, int variant, hipStream_t s);
+bool attention_bf16_variant_ok(int variant);
+hipError_t launch_edit_keys(const void* K_in, void* K_out, int B, int S, int Hkv, int D, int dtype,
+                            const SteerArgs& steer, hipStream_t s);
+size_t route_workspace_bytes(int B, int Hkv, int D, int t0, int t1);
+hipError_t launch_route(const void* Q, int B, int S, int Hq, int Hkv, int D, int dtype, const float* proto,
+                        int M, int t0, int t1, int mode, float tau, float* w_out, void* workspace,
+                        hipStream_t s);
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+}  // namespace seka

@@ -1,0 +1,253 @@
+// seka_edit_keys: standalone key-editing hook (paper Algorithm 1/2, inference part):
+//   k' = k + g * sum_m w_m U_m (U_m^T k)   on highlighted tokens of selected heads.
+//
+// HBM-bound (read K once, write K' once).  bf16 path: one workgroup = 64 tokens of one KV head,
+// one wave = 16 tokens.  A wave keeps its 16 x D key tile in registers in exactly the layout the
+// 16x16x32 bf16 MFMA wants for its B operand, so the two small GEMMs
+//   Z^T = U_cat^T K^T   (R x 16, contraction over D)      and
+//   C^T = U_cat (c .* Z^T)   (D x 16, contraction over R)
+// run on the matrix cores without moving the keys again, and the correction lands in the same
+// lanes that hold the matching key elements (the row order of U fed to the second GEMM is
+// permuted to make that so).  Tiles without highlighted tokens are a plain 16-byte copy (or are
+// skipped entirely when editing in place).  U is staged in LDS only by workgroups that need it.
+#include "common.h"
+
+namespace seka {
+
+namespace {
+
+constexpr int kEditThreads = 256;
+constexpr int kEditTokens = 64;   // tokens per workgroup (bf16 path)
+
+__device__ __forceinline__ int perm_col(int r) {
+  // position of U's column r inside its group of 32 so that one 16-byte LDS read yields the
+  // 8 contraction slots an MFMA lane owns: slot order follows the 16x16 accumulator layout
+  // (4 consecutive rows per lane per 16-row block).
+  return (r & ~31) + 8 * ((r & 15) >> 2) + 4 * ((r & 31) >> 4) + (r & 3);
+}
+
+template <int D>
+__global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint16_t* __restrict__ K_in,
+                                                                      uint16_t* __restrict__ K_out, int S, int Hkv,
+                                                                      SteerArgs st, int inplace, int Rpad) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int UT_LD = D + 8;                 // row stride of U^T [Rpad][D] in elements
+  const int UN_LD = Rpad + 8;                  // row stride of U (column-permuted) [D][Rpad]
+  uint16_t* UT = reinterpret_cast<uint16_t*>(smem);
+  uint16_t* UN = UT + (size_t)Rpad * UT_LD;
+  float* cvec = reinterpret_cast<float*>(UN + (size_t)D * UN_LD);
+
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int j = lane & 15, g = lane >> 4;
+  const int t = blockIdx.x * kEditTokens + wave * 16 + j;
+  const bool valid = t < S;
+  const int mk = valid ? st.mask[(size_t)b * S + t] : 0;
+  const float gain = st.gain[h];
+  const bool wave_hl = __ballot(mk != 0) != 0ull;
+  const bool block_hl = __syncthreads_or(mk != 0) != 0;
+  const bool steered = block_hl && gain != 0.f;
+
+  constexpr int KS = D / 32;
+  bf16x8 kreg[KS];
+  const size_t row_off = (((size_t)b * S + (valid ? t : 0)) * Hkv + h) * D;
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    uint4 v = make_uint4(0, 0, 0, 0);
+    if (valid) v = *reinterpret_cast<const uint4*>(K_in + row_off + 32 * s + 8 * g);
+    kreg[s] = __builtin_bit_cast(bf16x8, v);
+  }
+
+  if (!steered) {
+    if (!inplace && valid) {
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+        *reinterpret_cast<uint4*>(K_out + row_off + 32 * s + 8 * g) = __builtin_bit_cast(uint4, kreg[s]);
+    }
+    return;
+  }
+
+  // ---- stage U (both orientations) and the per-column coefficients in LDS ----
+  const int R = st.M * st.r;
+  if (R != Rpad) {
+    for (int i = threadIdx.x; i < (Rpad - R) * UT_LD; i += kEditThreads) UT[(size_t)R * UT_LD + i] = 0;
+    for (int i = threadIdx.x; i < D * UN_LD; i += kEditThreads) UN[i] = 0;
+    __syncthreads();
+  }
+  {
+    const uint16_t* Uh = reinterpret_cast<const uint16_t*>(st.U) + (size_t)h * st.M * D * st.r;
+    const int r8 = st.r / 8;
+    const int total = st.M * D * r8;
+    for (int idx = threadIdx.x; idx < total; idx += kEditThreads) {
+      const int m = idx / (D * r8), rem = idx % (D * r8);
+      const int d = rem / r8, v = rem % r8;
+      const uint4 u = *reinterpret_cast<const uint4*>(Uh + ((size_t)m * D + d) * st.r + 8 * v);
+      const int r0 = m * st.r + 8 * v;
+      const uint32_t wds[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        UT[(size_t)(r0 + e) * UT_LD + d] = (uint16_t)((wds[e >> 1] >> (16 * (e & 1))) & 0xffffu);
+      *reinterpret_cast<uint2*>(UN + (size_t)d * UN_LD + perm_col(r0)) = make_uint2(u.x, u.y);
+      *reinterpret_cast<uint2*>(UN + (size_t)d * UN_LD + perm_col(r0 + 4)) = make_uint2(u.z, u.w);
+    }
+    for (int r = threadIdx.x; r < Rpad; r += kEditThreads) {
+      float c = 0.f;
+      if (r < R) c = gain * (st.w ? st.w[((size_t)b * Hkv + h) * st.M + r / st.r] : 1.f);
+      cvec[r] = c;
+    }
+  }
+  __syncthreads();
+
+  if (!wave_hl) {
+    if (!inplace && valid) {
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+        *reinterpret_cast<uint4*>(K_out + row_off + 32 * s + 8 * g) = __builtin_bit_cast(uint4, kreg[s]);
+    }
+    return;
+  }
+
+  // ---- Z^T = U^T K^T, scaled by c_r and by the token's mask bit; packed as the next B operand ----
+  const float mbit = mk != 0 ? 1.f : 0.f;
+  constexpr int MAXKS2 = SEKA_MAX_RANK / 32;
+  bf16x8 zb[MAXKS2];
+  const int nks2 = Rpad / 32;
+#pragma unroll
+  for (int ks2 = 0; ks2 < MAXKS2; ++ks2) {
+    if (ks2 < nks2) {
+      float zc[8];
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const int rb = 2 * ks2 + half;
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(UT + (size_t)(16 * rb + j) * UT_LD + 32 * s + 8 * g);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, kreg[s], acc, 0, 0, 0);
+        }
+        const f32x4 c4 = *reinterpret_cast<const f32x4*>(cvec + 16 * rb + 4 * g);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) zc[4 * half + i] = acc[i] * c4[i] * mbit;
+      }
+      bf16x8 z;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) z[e] = (__bf16)zc[e];
+      zb[ks2] = z;
+    }
+  }
+
+  // ---- C^T = U (c .* Z^T); rows of U are visited in the order that puts d = 32 s + 8 g + e in lane (j, g) ----
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    float outv[8];
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const int d_row = 32 * s + 8 * (j >> 2) + 4 * half + (j & 3);
+      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks2 = 0; ks2 < MAXKS2; ++ks2) {
+        if (ks2 < nks2) {
+          const bf16x8 a = *reinterpret_cast<const bf16x8*>(UN + (size_t)d_row * UN_LD + 32 * ks2 + 8 * g);
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, zb[ks2], acc, 0, 0, 0);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i) outv[4 * half + i] = (float)kreg[s][4 * half + i] + acc[i];
+    }
+    bf16x8 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (__bf16)outv[e];
+    if (valid && (!inplace || mk != 0))
+      *reinterpret_cast<uint4*>(K_out + row_off + 32 * s + 8 * g) = __builtin_bit_cast(uint4, o);
+  }
+}
+
+// fp32 path (small problems, exactness over speed): one workgroup = 16 tokens of one KV head.
+template <int D>
+__global__ __launch_bounds__(kEditThreads) void edit_keys_f32_kernel(const float* __restrict__ K_in,
+                                                                     float* __restrict__ K_out, int S, int Hkv,
+                                                                     SteerArgs st, int inplace) {
+  constexpr int TT = 16;
+  __shared__ float ktile[TT][D];
+  __shared__ float z[TT][SEKA_MAX_RANK];
+  __shared__ int mtile[TT];
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int t0 = blockIdx.x * TT;
+  const float gain = st.gain[h];
+  const int R = st.M * st.r;
+  int any = 0;
+  if (threadIdx.x < TT) {
+    const int t = t0 + threadIdx.x;
+    const int mk = (t < S) ? st.mask[(size_t)b * S + t] : 0;
+    mtile[threadIdx.x] = mk;
+    any = mk != 0;
+  }
+  const bool steered = __syncthreads_or(any) != 0 && gain != 0.f;
+  for (int i = threadIdx.x; i < TT * D; i += kEditThreads) {
+    const int tt = i / D, d = i % D, t = t0 + tt;
+    ktile[tt][d] = (t < S) ? K_in[(((size_t)b * S + t) * Hkv + h) * D + d] : 0.f;
+  }
+  __syncthreads();
+  if (steered) {
+    const float* Uh = static_cast<const float*>(st.U) + (size_t)h * st.M * D * st.r;
+    for (int i = threadIdx.x; i < TT * R; i += kEditThreads) {
+      const int tt = i / R, r = i % R, m = r / st.r, rr = r % st.r;
+      float acc = 0.f;
+      if (mtile[tt]) {
+        const float* u = Uh + (size_t)m * D * st.r + rr;
+        for (int d = 0; d < D; ++d) acc = fmaf(u[(size_t)d * st.r], ktile[tt][d], acc);
+        acc *= gain * (st.w ? st.w[((size_t)b * Hkv + h) * st.M + m] : 1.f);
+      }
+      z[tt][r] = acc;
+    }
+    __syncthreads();
+  }
+  for (int i = threadIdx.x; i < TT * D; i += kEditThreads) {
+    const int tt = i / D, d = i % D, t = t0 + tt;
+    if (t >= S) continue;
+    float v = ktile[tt][d];
+    const bool edited = steered && mtile[tt];
+    if (edited) {
+      const float* Uh = static_cast<const float*>(st.U) + (size_t)h * st.M * D * st.r;
+      float acc = 0.f;
+      for (int r = 0; r < R; ++r) {
+        const int m = r / st.r, rr = r % st.r;
+        acc = fmaf(Uh[((size_t)m * D + d) * st.r + rr], z[tt][r], acc);
+      }
+      v += acc;
+    }
+    if (!inplace || edited) K_out[(((size_t)b * S + t) * Hkv + h) * D + d] = v;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_edit_keys(const void* K_in, void* K_out, int B, int S, int Hkv, int D, int dtype,
+                            const SteerArgs& steer, hipStream_t s) {
+  const int inplace = (K_in == K_out) ? 1 : 0;
+  if (dtype == SEKA_BF16) {
+    const int R = steer.M * steer.r;
+    const int Rpad = (R + 31) / 32 * 32;
+    const size_t smem = ((size_t)Rpad * (D + 8) + (size_t)D * (Rpad + 8)) * 2 + (size_t)Rpad * 4;
+    const dim3 grid((S + kEditTokens - 1) / kEditTokens, Hkv, B);
+    auto launch = [&](auto kernel) -> hipError_t {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL(kernel, grid, dim3(kEditThreads), smem, s, static_cast<const uint16_t*>(K_in),
+                         static_cast<uint16_t*>(K_out), S, Hkv, steer, inplace, Rpad);
+      return hipGetLastError();
+    };
+    return D == 128 ? launch(edit_keys_bf16_kernel<128>) : launch(edit_keys_bf16_kernel<64>);
+  }
+  const dim3 grid((S + 15) / 16, Hkv, B);
+  if (D == 128)
+    hipLaunchKernelGGL(edit_keys_f32_kernel<128>, grid, dim3(kEditThreads), 0, s, static_cast<const float*>(K_in),
+                       static_cast<float*>(K_out), S, Hkv, steer, inplace);
+  else
+    hipLaunchKernelGGL(edit_keys_f32_kernel<64>, grid, dim3(kEditThreads), 0, s, static_cast<const float*>(K_in),
+                       static_cast<float*>(K_out), S, Hkv, steer, inplace);
+  return hipGetLastError();
+}
+
+}  // namespace seka

@@ -1,0 +1,114 @@
+"""C-ABI checks that need no GPU: the library loads, exports every declared symbol, and rejects
+bad arguments on the host before any launch."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2603_01281_amd import binding
+    return binding
+
+
+def test_exports_every_declared_symbol(B):
+    header = open(os.path.join(ROOT, "include", "seka.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(seka_[a-z_0-9]+)\s*\(", header))
+    assert {"seka_route", "seka_edit_keys", "seka_attention_prefill", "seka_attention_plain",
+            "seka_route_workspace_bytes", "seka_status_string", "seka_set_tuning"} <= names
+    for n in names:
+        assert hasattr(B.lib, n), f"libseka.so does not export {n}"
+
+
+def test_status_strings(B):
+    seen = set()
+    for code in range(0, 9):
+        s = B.lib.seka_status_string(code)
+        assert s and s not in seen
+        seen.add(s)
+    assert B.lib.seka_status_string(1234) == b"unknown status"
+
+
+FAKE = 0x10000   # aligned, never dereferenced: validation fails before any launch
+
+
+def _shape(B, **kw):
+    d = dict(B=1, S=128, Hq=4, Hkv=2, D=64, dtype=B.SEKA_F32, softmax_scale=0.0)
+    d.update(kw)
+    return B.seka_shape(d["B"], d["S"], d["Hq"], d["Hkv"], d["D"], d["dtype"], d["softmax_scale"])
+
+
+def _steer(B, Hkv=2, **kw):
+    gains = (ctypes.c_float * Hkv)(*([1.0] * Hkv))
+    d = dict(M=1, r=8, U=FAKE, w=None, gain=gains, mask=FAKE)
+    d.update(kw)
+    st = B.seka_steer(d["M"], d["r"], d["U"], d["w"], d["gain"], d["mask"])
+    st._keep = gains
+    return st
+
+
+def test_attention_rejects_bad_arguments(B):
+    L = B.lib
+    ok = _shape(B)
+    call = lambda q, k, v, o, sh: L.seka_attention_plain(q, k, v, o, None, ctypes.byref(sh), None)
+    assert call(None, FAKE, FAKE, FAKE, ok) == 1                      # NULL
+    assert call(FAKE, FAKE, FAKE, None, ok) == 1
+    assert L.seka_attention_plain(FAKE, FAKE, FAKE, FAKE, None, None, None) == 1
+    assert call(FAKE, FAKE, FAKE, FAKE * 4, _shape(B, D=96)) == 2     # head dim
+    assert call(FAKE, FAKE, FAKE, FAKE * 4, _shape(B, Hq=5)) == 2     # Hq % Hkv
+    assert call(FAKE, FAKE, FAKE, FAKE * 4, _shape(B, S=0)) == 2
+    assert call(FAKE, FAKE, FAKE, FAKE * 4, _shape(B, Hkv=128, Hq=128)) == 2
+    assert call(FAKE, FAKE, FAKE, FAKE * 4, _shape(B, dtype=7)) == 3  # dtype
+    assert call(FAKE + 4, FAKE, FAKE, FAKE * 4, ok) == 4              # alignment
+    assert call(FAKE, FAKE, FAKE, FAKE, ok) == 5                      # O aliases Q
+    assert call(FAKE * 4, FAKE, FAKE * 8, FAKE + 64, ok) == 5         # O overlaps K
+
+
+def test_steering_rejects_bad_arguments(B):
+    L = B.lib
+    ok = _shape(B)
+    far = FAKE * 64
+    call = lambda st, sh=ok: L.seka_attention_prefill(FAKE, FAKE * 4, FAKE * 8, far, None, ctypes.byref(sh), ctypes.byref(st), None)
+    assert call(_steer(B, U=None)) == 1
+    assert call(_steer(B, M=0)) == 2
+    assert call(_steer(B, M=4, r=64)) == 2          # M*r > 128
+    assert call(_steer(B, r=80)) == 2               # r > D
+    assert call(_steer(B, U=FAKE + 2)) == 4
+    bad_gain = (ctypes.c_float * 2)(1.0, float("nan"))
+    assert call(_steer(B, gain=bad_gain)) == 2
+    bf = _shape(B, dtype=B.SEKA_BF16)
+    assert call(_steer(B, r=5), bf) == 6            # bf16 needs r % 8 == 0
+    # edit_keys: partial overlap of input and output
+    st = _steer(B)
+    assert L.seka_edit_keys(FAKE, FAKE + 64, ctypes.byref(ok), ctypes.byref(st), None) == 5
+    assert L.seka_edit_keys(FAKE, None, ctypes.byref(ok), ctypes.byref(st), None) == 1
+    assert L.seka_edit_keys(FAKE, FAKE, ctypes.byref(ok), None, None) == 1
+
+
+def test_route_rejects_bad_arguments(B):
+    L = B.lib
+    ok = _shape(B)
+    need = L.seka_route_workspace_bytes(ctypes.byref(ok), 0, 128)
+    assert need > 0 and need % 16 == 0
+    assert L.seka_route_workspace_bytes(ctypes.byref(ok), 5, 5) == 0
+    call = lambda **kw: L.seka_route(kw.get("Q", FAKE), ctypes.byref(kw.get("sh", ok)), kw.get("proto", FAKE * 2), kw.get("M", 4),
+                                     kw.get("t0", 0), kw.get("t1", 128), kw.get("mode", 0), kw.get("tau", 10.0),
+                                     kw.get("w", FAKE * 3), kw.get("ws", FAKE * 5), kw.get("wsb", need), None)
+    assert call(Q=None) == 1
+    assert call(M=0) == 2 and call(M=17) == 2
+    assert call(t0=10, t1=10) == 2 and call(t1=129) == 2 and call(t0=-1) == 2
+    assert call(mode=9) == 6
+    assert call(tau=float("inf")) == 2
+    assert call(ws=None) == 8 and call(wsb=need - 1) == 8
+    assert call(ws=FAKE * 5 + 8) == 4
+
+
+def test_tuning_rejects_unknown(B):
+    assert B.lib.seka_set_tuning(99, 0) == 6
+    assert B.lib.seka_set_tuning(0, 12345) == 6
+    assert B.lib.seka_set_tuning(0, 0) == 0

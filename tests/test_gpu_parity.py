@@ -43,12 +43,17 @@ def test_cfg1_fp32_exact_config(seka):
     got_O, got_L = _run_attention(seka, dev, True)
     H.assert_close_f32(got_O, ref_O, "cfg1 steered O")
     H.assert_close_f32(got_L, ref_L, "cfg1 steered LSE")
-    ref_O, ref_L = orc.causal_attention(o["Q"], o["K"], o["V"], scale=inp.scale)
-    got_O, got_L = _run_attention(seka, dev, False)
-    H.assert_close_f32(got_O, ref_O, "cfg1 plain O")
-    H.assert_close_f32(got_L, ref_L, "cfg1 plain LSE")
-    # steering must actually change the result here
-    assert np.abs(got_O - orc.steered_attention(o["Q"], o["K"], o["V"], o["U"], inp.gain, inp.mask, scale=inp.scale)[0]).max() > 1e-3
+    ref_P, ref_PL = orc.causal_attention(o["Q"], o["K"], o["V"], scale=inp.scale)
+    got_P, got_PL = _run_attention(seka, dev, False)
+    H.assert_close_f32(got_P, ref_P, "cfg1 plain O")
+    H.assert_close_f32(got_PL, ref_PL, "cfg1 plain LSE")
+    # With inputs scaled by 1/8 the steering moves O by only ~1e-4 here, i.e. by about the stated
+    # tolerance; fp32 arithmetic on values of this size is good to ~1e-6, so also hold the kernel to
+    # that, which separates steered from unsteered by a wide margin.
+    effect = np.abs(ref_O - ref_P).max()
+    assert effect > 5e-5
+    H.assert_close_f32(got_O, ref_O, "cfg1 steered O (tight)", tol=2e-6)
+    H.assert_close_f32(got_P, ref_P, "cfg1 plain O (tight)", tol=2e-6)
 
 
 @pytest.mark.parametrize("case", [
@@ -106,11 +111,11 @@ def test_bf16_attention_small(seka, name, variant):
     ref_O, ref_L = orc.steered_attention(o["Q"], o["K"], o["V"], o["U"], inp.gain, inp.mask, scale=inp.scale)
     got_O, got_L = _run_attention(seka, dev, True, variant)
     H.assert_close_bf16(got_O, ref_O, f"{name} steered O")
-    H.assert_close_f32(got_L, ref_L, f"{name} steered LSE", tol=5e-3)
+    H.assert_lse_close_bf16(got_L, ref_L, f"{name} steered LSE")
     ref_P, ref_PL = orc.causal_attention(o["Q"], o["K"], o["V"], scale=inp.scale)
     got_P, got_PL = _run_attention(seka, dev, False, variant)
     H.assert_close_bf16(got_P, ref_P, f"{name} plain O")
-    H.assert_close_f32(got_PL, ref_PL, f"{name} plain LSE", tol=5e-3)
+    H.assert_lse_close_bf16(got_PL, ref_PL, f"{name} plain LSE")
     assert np.abs(ref_O - ref_P).max() > 5e-2, "steering has no visible effect in this case: test is vacuous"
 
 
@@ -198,7 +203,7 @@ def test_bf16_tiny_lengths(seka, S):
     for variant in (0, 1):
         got_O, got_L = _run_attention(seka, dev, True, variant)
         H.assert_close_bf16(got_O, ref_O, f"S={S} O")
-        H.assert_close_f32(got_L, ref_L, f"S={S} LSE", tol=5e-3)
+        H.assert_lse_close_bf16(got_L, ref_L, f"S={S} LSE")
 
 
 def test_degenerate_steering_equals_plain(seka):

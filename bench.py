@@ -1,0 +1,221 @@
+#!/usr/bin/env python3
+"""Benchmark of the SEKA prefill hot path on one MI355X.
+
+One step = one pass of the whole hot path over benchmark configuration 3: a Llama-3-8B-shaped 32-layer
+prefill stack (B=4, S=8192, 32 query heads, 8 KV heads, D=128, bf16): layers 8..23 run
+seka_attention_prefill (key edit fused in, distinct rank-32 U per (layer, KV head), per-layer gain
+~U[0.25, 2], highlighted spans covering 5-20% of each sequence), the other 16 layers run
+seka_attention_plain.  Inputs are seeded synthetic tensors resident in HBM before the timed region.
+
+Prints ONE JSON line: whole-job TFLOP/s (causal-pair convention 4*D per visible (query, key) pair; edit flops
+are not credited), the MFMA roofline of the dominant kernel (the fused steered attention launch, timed
+with events on its own stream inside the timed region) and the CPU oracle timed on a bounded sample.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--layers", type=int, default=32, help=argparse.SUPPRESS)
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the CPU oracle leg (profiling runs)")
+    ap.add_argument("--copy-calib", action="store_true",
+                    help="also run one device copy of a known size (256 MiB read + 256 MiB written) so that "
+                         "hardware byte counters can be scaled against it")
+    ap.add_argument("--extras", action="store_true", help="also time configurations 2, 4, 5 (reported inside the same JSON line)")
+    return ap.parse_args()
+
+
+def attn_flops(B, S, Hq, D):
+    return 4.0 * D * B * Hq * (S * (S + 1) / 2.0)
+
+
+def build_stack(torch, inputs, L, seed=0):
+    """Per-layer device tensors of configuration 3.  Q/K/V are drawn on the device (seeded, N(0,1), bf16),
+    distinct for every layer; U, spans and gains come from the shared seeded generator."""
+    import numpy as np
+    shp = inputs.CONFIG_SHAPES[3]
+    B, S, Hq, Hkv, D, r = shp["B"], shp["S"], shp["Hq"], shp["Hkv"], shp["D"], shp["r"]
+    gains = inputs.layer_gains_cfg3(seed, layers=32)[:L] if L <= 32 else inputs.layer_gains_cfg3(seed, layers=L)
+    gen = torch.Generator(device="cuda")
+    layers = []
+    for l in range(L):
+        gen.manual_seed(1000003 * seed + l)
+        Q = torch.randn((B, S, Hq, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        K = torch.randn((B, S, Hkv, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        V = torch.randn((B, S, Hkv, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        O = torch.empty_like(Q)
+        item = dict(Q=Q, K=K, V=V, O=O, gain=float(gains[l]))
+        if gains[l] != 0:
+            U = inputs.orthonormal_bases(Hkv, 1, D, r, seed, "bf16", layer=l)
+            mask, spans = inputs.span_mask(B, S, seed, ("cover", 0.05, 0.20, 4), layer=l)
+            item["U"] = torch.from_numpy(U.view(np.int16)).view(torch.bfloat16).cuda()
+            item["mask"] = torch.from_numpy(mask).cuda()
+            item["cover"] = float(mask.mean())
+        layers.append(item)
+    return layers, (B, S, Hq, Hkv, D)
+
+
+def run_layer(seka, it, Hkv):
+    if it["gain"] != 0:
+        seka.seka_attention_prefill(it["Q"], it["K"], it["V"], it["O"], it["U"], [it["gain"]] * Hkv, it["mask"])
+    else:
+        seka.seka_attention_plain(it["Q"], it["K"], it["V"], it["O"])
+
+
+def cpu_baseline(inputs):
+    """The fp64 oracle, unmodified, on a bounded sample of the same workload: layer 8 (the first steered layer),
+    batch entry 0 (all 8 KV heads, 32 query heads), all 8192 tokens."""
+    import numpy as np
+    from oracle import seka_oracle as orc
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    shp = inputs.CONFIG_SHAPES[3]
+    S, D, G = shp["S"], shp["D"], shp["Hq"] // shp["Hkv"]
+    inp = inputs.make_layer("cfg3-sample", "bf16", B=1, S=S, Hq=shp["Hq"], Hkv=shp["Hkv"], D=D, M=1, r=shp["r"],
+                            gain=float(inputs.layer_gains_cfg3(0)[8]), mask_recipe=("cover", 0.05, 0.20, 4), seed=0, layer=8)
+    Q, K, V, U = inp.widen(inp.Q), inp.widen(inp.K), inp.widen(inp.V), inp.widen(inp.U)
+    t0 = time.perf_counter()
+    orc.steered_attention(Q, K, V, U, inp.gain, inp.mask, scale=inp.scale)
+    dt = time.perf_counter() - t0
+    fl = attn_flops(1, S, shp["Hq"], D)
+    return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle", "seconds": round(dt, 2),
+            "sample": "cfg3 layer 8, batch entry 0 (8 KV heads, 32 query heads), all 8192 tokens "
+                      "(1/4 of one layer, 1/128 of a step); same causal-pair flop convention"}
+
+
+def time_config(torch, seka, inputs, cfg, iters=10):
+    """Mean event-timed latency of plain and steered attention at another benchmark configuration (device-drawn inputs)."""
+    import numpy as np
+    shp = inputs.CONFIG_SHAPES[cfg]
+    B, S, Hq, Hkv, D, M, r = (shp[k] for k in ("B", "S", "Hq", "Hkv", "D", "M", "r"))
+    gen = torch.Generator(device="cuda"); gen.manual_seed(cfg)
+    mk = lambda h: torch.randn((B, S, h, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    Q, K, V = mk(Hq), mk(Hkv), mk(Hkv)
+    O = torch.empty_like(Q)
+    U = torch.from_numpy(inputs.orthonormal_bases(Hkv, M, D, r, 0, "bf16").view(np.int16)).view(torch.bfloat16).cuda()
+    recipe = {2: ("cover", 0.10, 0.10, 3), 4: ("cover", 0.10, 0.10, 3), 5: ("lengths", 8, 64, 512)}[cfg]
+    mask = torch.from_numpy(inputs.span_mask(B, S, 0, recipe)[0]).cuda()
+    gain = [{2: 1.0, 4: 1.0, 5: 1.5}[cfg]] * Hkv
+    w = None
+    route_ms = None
+    if M > 1:
+        proto = torch.from_numpy(inputs.unit_prototypes(Hkv, M, D, 0)).cuda()
+        w = seka.seka_route(Q, proto, 0, S, seka.SEKA_ROUTE_SOFTMAX_COS, 10.0)
+        ws = torch.empty(seka.seka_route_workspace_bytes(B, S, Hq, Hkv, D, seka.SEKA_BF16, 0, S), dtype=torch.uint8, device="cuda")
+        route_ms = event_time(torch, lambda: seka.seka_route(Q, proto, 0, S, seka.SEKA_ROUTE_SOFTMAX_COS, 10.0, w_out=w, workspace=ws), iters)
+    plain = event_time(torch, lambda: seka.seka_attention_plain(Q, K, V, O), iters)
+    steer = event_time(torch, lambda: seka.seka_attention_prefill(Q, K, V, O, U, gain, mask, w=w), iters)
+    fl = attn_flops(B, S, Hq, D)
+    out = {"plain_ms": round(plain, 4), "steered_ms": round(steer, 4), "steered_tflops": round(fl / steer / 1e9, 1),
+           "overhead_pct": round(100 * (steer / plain - 1), 2), "tokens_per_s": round(B * S / steer * 1e3)}
+    if route_ms is not None:
+        out["route_ms"] = round(route_ms, 4)
+        out["route_GBps"] = round(B * S * Hq * D * 2 / route_ms / 1e6, 1)
+    return out
+
+
+def event_time(torch, fn, iters, warm=3):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2603_01281_amd import binding as seka, inputs
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    layers, (B, S, Hq, Hkv, D) = build_stack(torch, inputs, args.layers)
+    L = len(layers)
+    steered_ix = [i for i, it in enumerate(layers) if it["gain"] != 0]
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        for it in layers:
+            run_layer(seka, it, Hkv)
+    torch.cuda.synchronize()
+
+    # timed region: exactly K steps; every launch is bracketed by events on the launch stream
+    ev = [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(L)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        for i, it in enumerate(layers):
+            ev[k][i][0].record()
+            run_layer(seka, it, Hkv)
+            ev[k][i][1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+
+    ms_per_step = wall * 1e3 / args.steps
+    fl_layer = attn_flops(B, S, Hq, D)
+    value = fl_layer * L / (ms_per_step * 1e-3) / 1e12
+    per_layer = [sum(ev[k][i][0].elapsed_time(ev[k][i][1]) for k in range(args.steps)) / args.steps for i in range(L)]
+    st_ms = sum(per_layer[i] for i in steered_ix) / max(1, len(steered_ix))
+    pl = [per_layer[i] for i in range(L) if i not in steered_ix]
+    pl_ms = sum(pl) / max(1, len(pl))
+    achieved = fl_layer / (st_ms * 1e-3) / 1e12 if steered_ix else fl_layer / (pl_ms * 1e-3) / 1e12
+
+    out = {
+        "metric": "steered_prefill_attention_tflops", "value": round(value, 2), "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"cfg3: Llama-3-8B-shaped {L}-layer SEKA prefill stack, B={B} S={S} Hq={Hq} Hkv={Hkv} D={D}, "
+                               f"rank-32 U per (layer, KV head), layers 8-23 steered ({len(steered_ix)} fused + {L - len(steered_ix)} plain launches per step)",
+                   "global_batch": B, "seq_len": S, "layers": L},
+        "pct_of_bf16_mfma_peak": round(100 * value / PEAK_BF16_TFLOPS, 2),
+        "tokens_per_s": round(B * S * L / (ms_per_step * 1e-3)),
+        "steered_layer_ms": round(st_ms, 4), "plain_layer_ms": round(pl_ms, 4),
+        "steering_overhead_pct": round(100 * (st_ms / pl_ms - 1), 2) if pl and steered_ix else None,
+        "roofline": {"bound": "mfma", "kernel": "attention_bf16_kernel<D=128, 4 heads x 64 rows, STEER> (seka_attention_prefill)",
+                     "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "flops_per_launch": fl_layer, "launch_ms": round(st_ms, 4)},
+    }
+    if args.copy_calib:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    if args.extras:
+        out["other_configs"] = {f"cfg{c}": time_config(torch, seka, inputs, c) for c in (2, 4, 5)}
+    del layers
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(inputs)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -126,6 +126,10 @@ seka_status seka_attention_plain(const void* Q, const void* K, const void* V, vo
 /* Name of a status code; static storage, never NULL. */
 const char* seka_status_string(int32_t status);
 
+/* HIP runtime's description of the calling thread's most recent launch result ("no error" after a
+ * success); for diagnosing SEKA_ERR_LAUNCH.  Static storage, never NULL. */
+const char* seka_last_launch_error(void);
+
 /*
  * seka_set_tuning — select among kernel variants that compute the same result (for benchmarks).
  * key 0: bf16 attention variant id (0 = library default).  Unknown keys/values return

@@ -8,6 +8,11 @@ Importing this module raises if the shared library has not been built
 import ctypes
 import os
 
+# PyTorch ships its own HIP runtime (same soname as the system one).  Loading it first makes the
+# library below share that runtime, so device pointers and stream handles mean the same thing to
+# both; the other order leaves this process with a runtime that reports no device to our launches.
+import torch  # noqa: F401  (must precede the CDLL call)
+
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libseka.so")
 
@@ -37,6 +42,8 @@ _shape_p, _steer_p = ctypes.POINTER(seka_shape), ctypes.POINTER(seka_steer)
 
 lib.seka_status_string.restype = ctypes.c_char_p
 lib.seka_status_string.argtypes = [_i32]
+lib.seka_last_launch_error.restype = ctypes.c_char_p
+lib.seka_last_launch_error.argtypes = []
 lib.seka_set_tuning.restype = _i32
 lib.seka_set_tuning.argtypes = [_i32, _i32]
 lib.seka_route_workspace_bytes.restype = _sz
@@ -54,7 +61,8 @@ lib.seka_attention_plain.argtypes = [_vp, _vp, _vp, _vp, _vp, _shape_p, _vp]
 class SekaError(RuntimeError):
     def __init__(self, status):
         self.status = status
-        super().__init__(f"seka status {status}: {lib.seka_status_string(status).decode()}")
+        detail = f" ({lib.seka_last_launch_error().decode()})" if status == 7 else ""
+        super().__init__(f"seka status {status}: {lib.seka_status_string(status).decode()}{detail}")
 
 
 def _check(status):
@@ -63,7 +71,6 @@ def _check(status):
 
 
 def _torch():
-    import torch
     return torch
 
 

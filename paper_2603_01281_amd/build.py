@@ -15,6 +15,7 @@ SOURCES = ["api.hip", "route.hip", "edit.hip", "attn_f32.hip", "attn_bf16.hip", 
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffast-math", "-fno-finite-math-only",
+    "-Wno-inline-asm",                                                # m0 is clobbered on purpose by the direct-to-LDS loads
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",      # packed fp32 VALU forms are kept out on purpose
     "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]

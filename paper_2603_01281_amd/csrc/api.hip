@@ -8,6 +8,13 @@
 namespace {
 
 int g_attn_bf16_variant = 0;
+thread_local hipError_t g_last_hip_error = hipSuccess;
+
+seka_status launch_status(hipError_t e) {
+  g_last_hip_error = e;
+  if (e == hipSuccess) return SEKA_OK;
+  return e == hipErrorNotSupported ? SEKA_ERR_UNSUPPORTED : SEKA_ERR_LAUNCH;
+}
 
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
@@ -80,11 +87,11 @@ seka_status attention_common(const void* Q, const void* K, const void* V, void* 
   a.B = sh->B; a.S = sh->S; a.Hq = sh->Hq; a.Hkv = sh->Hkv; a.D = sh->D;
   a.scale = sh->softmax_scale > 0.0f ? sh->softmax_scale : 1.0f / std::sqrt((float)sh->D);
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
+  (void)hipGetLastError();   // drop any stale error left by earlier, unrelated runtime calls of this thread
   hipError_t e = (sh->dtype == SEKA_BF16)
                      ? seka::launch_attention_bf16(a, steered ? &sa : nullptr, g_attn_bf16_variant, stream)
                      : seka::launch_attention_f32(a, steered ? &sa : nullptr, stream);
-  if (e == hipErrorNotSupported) return SEKA_ERR_UNSUPPORTED;
-  return e == hipSuccess ? SEKA_OK : SEKA_ERR_LAUNCH;
+  return launch_status(e);
 }
 
 }  // namespace
@@ -105,6 +112,8 @@ const char* seka_status_string(int32_t status) {
     default: return "unknown status";
   }
 }
+
+const char* seka_last_launch_error(void) { return hipGetErrorString(g_last_hip_error); }
 
 seka_status seka_set_tuning(int32_t key, int32_t value) {
   if (key == 0 && seka::attention_bf16_variant_ok(value)) {
@@ -133,9 +142,10 @@ seka_status seka_route(const void* Q, const seka_shape* sh, const float* proto, 
   const size_t need = seka::route_workspace_bytes(sh->B, sh->Hkv, sh->D, t0, t1);
   if (!workspace || workspace_bytes < need) return SEKA_ERR_WORKSPACE;
   if (misaligned(workspace)) return SEKA_ERR_ALIGN;
+  (void)hipGetLastError();
   hipError_t e = seka::launch_route(Q, sh->B, sh->S, sh->Hq, sh->Hkv, sh->D, sh->dtype, proto, M, t0, t1, mode,
                                     tau, w_out, workspace, reinterpret_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? SEKA_OK : SEKA_ERR_LAUNCH;
+  return launch_status(e);
 }
 
 seka_status seka_edit_keys(const void* K_in, void* K_out, const seka_shape* sh, const seka_steer* st,
@@ -150,9 +160,10 @@ seka_status seka_edit_keys(const void* K_in, void* K_out, const seka_shape* sh, 
   if (K_in != K_out && ranges_overlap(K_in, nk, K_out, nk)) return SEKA_ERR_ALIAS;
   seka::SteerArgs sa;
   fill_steer(sa, st, sh->Hkv);
+  (void)hipGetLastError();
   hipError_t e = seka::launch_edit_keys(K_in, K_out, sh->B, sh->S, sh->Hkv, sh->D, sh->dtype, sa,
                                         reinterpret_cast<hipStream_t>(hip_stream));
-  return e == hipSuccess ? SEKA_OK : SEKA_ERR_LAUNCH;
+  return launch_status(e);
 }
 
 seka_status seka_attention_prefill(const void* Q, const void* K, const void* V, void* O, float* lse,

@@ -11,9 +11,14 @@
 //                   A lane then owns ONE query row (column of S^T) and 32 of the tile's 64 keys,
 //                   so the row max/sum are in-lane reductions plus one exchange with lane^32.
 //   O^T = V^T P^T : B = P^T taken straight from the S^T accumulators (the contraction order over
-//                   keys is permuted identically on the V side), A = V^T fragments read from LDS
-//                   either with the transposing LDS read (VMODE 0) or from a tile that was
-//                   stored transposed (VMODE 1).
+//                   keys is permuted identically on the V side), A = V^T fragments fetched from the
+//                   row-major V tile with the transposing LDS read (ds_read_b64_tr_b16).
+// Ping-pong (MODE 1): a SIMD hosts two waves of the workgroup.  Both would otherwise run the same
+//   phase at the same time (matrix pipe idle while both exponentiate, vector ALU idle while both
+//   multiply).  The waves of the second half of the workgroup therefore run one phase ahead: they
+//   enter an iteration with S^T of the current tile already computed and order their work
+//   softmax -> PV -> next S^T, while the first half orders it S^T -> softmax -> PV.  K tiles live
+//   in three LDS buffers so that both the current and the next tile are readable.
 // Key edit (STEER): after a K tile lands in LDS, a wave ballot of its mask bytes tells whether it
 //   holds highlighted tokens; if so, 16-key blocks with highlights get
 //   Z^T = U_cat^T K^T and K'^T = K^T + U_cat (c .* Z^T) on 16x16x32 MFMAs, written back to LDS as bf16.
@@ -24,35 +29,36 @@ namespace seka {
 
 constexpr int ATT_BK = 64;   // keys per tile
 
-__host__ __device__ constexpr int att_kld(int D) { return D + 8; }                       // K tile row stride
-__host__ __device__ constexpr int att_v_elems(int D, int vmode) { return vmode == 0 ? ATT_BK * (D + 8) : D * (ATT_BK + 8); }
+__host__ __device__ constexpr int att_kld(int D) { return D + 8; }     // K tile row stride (elements)
+__host__ __device__ constexpr int att_nkb(int mode) { return mode >= 1 ? 3 : 2; }
 
-inline size_t attention_bf16_smem_bytes(int D, int vmode, bool steer, int Rpad) {
-  size_t n = 2 * ((size_t)ATT_BK * att_kld(D) + att_v_elems(D, vmode)) * 2;
-  if (steer) n += ((size_t)Rpad * (D + 8) + (size_t)D * (Rpad + 8)) * 2 + (size_t)Rpad * 4;
+inline size_t attention_bf16_smem_bytes(int D, int vpad, int mode, bool steer, int Rpad) {
+  size_t n = ((size_t)att_nkb(mode) * ATT_BK * att_kld(D) + 2 * (size_t)ATT_BK * (D + vpad)) * 2;
+  if (steer) n += (size_t)D * (Rpad + 8) * 2 + (size_t)Rpad * 4;
   return n;
 }
 
-__device__ __forceinline__ int att_perm_col(int r) {
-  return (r & ~31) + 8 * ((r & 15) >> 2) + 4 * ((r & 31) >> 4) + (r & 3);
+typedef __attribute__((address_space(3))) s16x4* lds_s16x4_ptr;
+
+__device__ __forceinline__ bf16x8 lds_read_tr_pair(const uint16_t* p0, const uint16_t* p1) {
+  // two transposing 64-bit LDS reads -> 8 contraction slots of an MFMA operand
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p0));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4_ptr)(p1));
+  const bf16x4 lo4 = __builtin_bit_cast(bf16x4, lo), hi4 = __builtin_bit_cast(bf16x4, hi);
+  return __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
-__device__ __forceinline__ int att_vslot(int j) {
-  // position of key j inside a transposed V row so that a lane's 8 contraction slots are contiguous
-  const int j16 = j & 15;
-  return (j & ~15) + 8 * ((j16 >> 2) & 1) + 4 * (j16 >> 3) + (j16 & 3);
-}
-
-template <int D, int HPW, int RB, bool STEER, int VMODE>
+template <int D, int HPW, int RB, bool STEER, int VPAD, int MODE, int ABL = 0>
 __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs a, SteerArgs st, int Rpad) {
   constexpr int NW = HPW * RB;
   constexpr int NT = 64 * NW;
   constexpr int BQ = 32 * RB;
   constexpr int BK = ATT_BK;
   constexpr int KLD = att_kld(D);
-  constexpr int VLD = VMODE == 0 ? D + 8 : BK + 8;
+  constexpr int VLD = D + VPAD;
   constexpr int K_ELEMS = BK * KLD;
-  constexpr int V_ELEMS = att_v_elems(D, VMODE);
+  constexpr int V_ELEMS = BK * VLD;
+  constexpr int NKB = att_nkb(MODE);  // K buffers in LDS
   constexpr int KS = D / 16;          // contraction steps of S^T = K Q^T
   constexpr int DB = D / 32;          // 32-row blocks of O^T
   constexpr int CPR = D / 8;          // 16-byte chunks per tile row
@@ -60,11 +66,11 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
   constexpr int NCH = (CHUNKS + NT - 1) / NT;
 
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  uint16_t* Kt = reinterpret_cast<uint16_t*>(smem);            // [2][BK][KLD]
-  uint16_t* Vt = Kt + 2 * K_ELEMS;                             // [2][V_ELEMS]
-  uint16_t* UT = Vt + 2 * V_ELEMS;                             // [Rpad][D+8]      (STEER)
-  uint16_t* UN = UT + (size_t)Rpad * (D + 8);                  // [D][Rpad+8]      (STEER, columns permuted)
-  float* cvec = reinterpret_cast<float*>(UN + (size_t)D * (Rpad + 8));
+  uint16_t* Kt = reinterpret_cast<uint16_t*>(smem);            // [NKB][BK][KLD]
+  uint16_t* Vt = Kt + NKB * K_ELEMS;                           // [2][BK][VLD]
+  uint16_t* UN = Vt + 2 * V_ELEMS;                             // [D][Rpad+8]   U_cat, row d, column r (STEER)
+  const int ULD = Rpad + 8;
+  float* cvec = reinterpret_cast<float*>(UN + (size_t)D * ULD);   // [Rpad]  c_r = g * w_m(r)
 
   const uint16_t* __restrict__ Qg = static_cast<const uint16_t*>(a.Q);
   const uint16_t* __restrict__ Kg = static_cast<const uint16_t*>(a.K);
@@ -104,12 +110,11 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
     }
   }
 
-  // ---- stage U (both orientations) and coefficients ----
+  // ---- stage U_cat (as stored: row d, r contiguous) and the per-column coefficients ----
   if (STEER && steer_on) {
     const int R = st.M * st.r;
     if (R != Rpad) {
-      for (int i = tid; i < (Rpad - R) * (D + 8); i += NT) UT[(size_t)R * (D + 8) + i] = 0;
-      for (int i = tid; i < D * (Rpad + 8); i += NT) UN[i] = 0;
+      for (int i = tid; i < D * ULD; i += NT) UN[i] = 0;
       __syncthreads();
     }
     const uint16_t* Uh = static_cast<const uint16_t*>(st.U) + (size_t)h * st.M * D * st.r;
@@ -118,75 +123,56 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
     for (int idx = tid; idx < total; idx += NT) {
       const int m = idx / (D * r8), rm = idx % (D * r8);
       const int d = rm / r8, v = rm % r8;
-      const uint4 u = *reinterpret_cast<const uint4*>(Uh + ((size_t)m * D + d) * st.r + 8 * v);
-      const int r0 = m * st.r + 8 * v;
-      const uint32_t wds[4] = {u.x, u.y, u.z, u.w};
-#pragma unroll
-      for (int e = 0; e < 8; ++e)
-        UT[(size_t)(r0 + e) * (D + 8) + d] = (uint16_t)((wds[e >> 1] >> (16 * (e & 1))) & 0xffffu);
-      *reinterpret_cast<uint2*>(UN + (size_t)d * (Rpad + 8) + att_perm_col(r0)) = make_uint2(u.x, u.y);
-      *reinterpret_cast<uint2*>(UN + (size_t)d * (Rpad + 8) + att_perm_col(r0 + 4)) = make_uint2(u.z, u.w);
+      *reinterpret_cast<uint4*>(UN + (size_t)d * ULD + m * st.r + 8 * v) =
+          *reinterpret_cast<const uint4*>(Uh + ((size_t)m * D + d) * st.r + 8 * v);
     }
     for (int r = tid; r < Rpad; r += NT) {
       float c = 0.f;
       if (r < R) c = gain * (st.w ? st.w[((size_t)b * a.Hkv + h) * st.M + r / st.r] : 1.f);
       cvec[r] = c;
     }
-    // visibility of UT/UN/cvec is ensured by the barrier that follows the first tile write
+    // visibility of UN/cvec is ensured by the barrier that follows the first tile write
   }
 
   const int last_key = min(S, qb * BQ + BQ) - 1;
   const int ntiles = last_key / BK + 1;
 
+  // ---- tile movement: global -> registers -> LDS (K and V separately) ----
   uint4 kpre[NCH], vpre[NCH];
   int mpre = 0;
 
-  auto load_tile = [&](int t) {
+  auto load_rows = [&](const uint16_t* __restrict__ src, int t, uint4 (&dst)[NCH]) {
 #pragma unroll
     for (int n = 0; n < NCH; ++n) {
       const int c = tid + NT * n;
       const int row = c / CPR, cc = c % CPR;
       const int key = t * BK + row;
-      uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-      if ((NCH * NT == CHUNKS || c < CHUNKS) && key < S) {
-        const size_t off = (((size_t)b * S + key) * a.Hkv + h) * D + 8 * cc;
-        kv = *reinterpret_cast<const uint4*>(Kg + off);
-        vv = *reinterpret_cast<const uint4*>(Vg + off);
-      }
-      kpre[n] = kv;
-      vpre[n] = vv;
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if ((NCH * NT == CHUNKS || c < CHUNKS) && key < S)
+        v = *reinterpret_cast<const uint4*>(src + (((size_t)b * S + key) * a.Hkv + h) * D + 8 * cc);
+      dst[n] = v;
     }
+  };
+  auto load_mask = [&](int t) {
     if (STEER && steer_on) {
       const int key = t * BK + lane;
       mpre = key < S ? st.mask[(size_t)b * S + key] : 0;
     }
   };
-
-  auto store_tile = [&](int buf) {
-    uint16_t* Kb = Kt + buf * K_ELEMS;
-    uint16_t* Vb = Vt + buf * V_ELEMS;
+  auto store_rows = [&](uint16_t* dst, int ld, const uint4 (&src)[NCH]) {
 #pragma unroll
     for (int n = 0; n < NCH; ++n) {
       const int c = tid + NT * n;
       if (NCH * NT == CHUNKS || c < CHUNKS) {
         const int row = c / CPR, cc = c % CPR;
-        *reinterpret_cast<uint4*>(Kb + row * KLD + 8 * cc) = kpre[n];
-        if (VMODE == 0) {
-          *reinterpret_cast<uint4*>(Vb + row * VLD + 8 * cc) = vpre[n];
-        } else {
-          const uint32_t wds[4] = {vpre[n].x, vpre[n].y, vpre[n].z, vpre[n].w};
-          const int slot = att_vslot(row);
-#pragma unroll
-          for (int e = 0; e < 8; ++e)
-            Vb[(8 * cc + e) * VLD + slot] = (uint16_t)((wds[e >> 1] >> (16 * (e & 1))) & 0xffffu);
-        }
+        *reinterpret_cast<uint4*>(dst + row * ld + 8 * cc) = src[n];
       }
     }
   };
+  auto tile_ballot = [&]() -> unsigned long long { return (STEER && steer_on) ? __ballot(mpre != 0) : 0ull; };
 
-  // Edit the highlighted 16-key blocks of the K tile in LDS buffer `buf`.
-  auto edit_tile = [&](int buf, unsigned long long bits) {
-    uint16_t* Kb = Kt + buf * K_ELEMS;
+  // Edit the highlighted 16-key blocks of the K tile at Kb (LDS); one wave per block.
+  auto edit_tile = [&](uint16_t* Kb, unsigned long long bits) {
     const int j = lane & 15, g = lane >> 4;
     constexpr int KS2 = D / 32;
     constexpr int MAXKR = SEKA_MAX_RANK / 32;
@@ -195,10 +181,12 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
       const unsigned bits16 = (unsigned)((bits >> (16 * kblk)) & 0xffffull);
       if (bits16 == 0) continue;
       uint16_t* krow = Kb + (16 * kblk + j) * KLD + 8 * g;
-      bf16x8 kreg[KS2];
+      bf16x8 kreg[KS2];   // K^T as B operand: lane (col = key j, k = d = 32 s + 8 g + e)
 #pragma unroll
       for (int s = 0; s < KS2; ++s) kreg[s] = *reinterpret_cast<const bf16x8*>(krow + 32 * s);
       const float mbit = ((bits16 >> j) & 1u) ? 1.f : 0.f;
+      // Z^T = U^T K^T: A = U^T (row r, k = d) read transposed from the row-d layout
+      const uint16_t* ut = UN + (size_t)(8 * g + (j >> 2)) * ULD + 4 * (j & 3);
       bf16x8 zb[MAXKR];
 #pragma unroll
       for (int kr = 0; kr < MAXKR; ++kr) {
@@ -210,19 +198,21 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < KS2; ++s) {
-              const bf16x8 ua = *reinterpret_cast<const bf16x8*>(UT + (size_t)(16 * rb + j) * (D + 8) + 32 * s + 8 * g);
+              const uint16_t* p = ut + (size_t)(32 * s) * ULD + 16 * rb;
+              const bf16x8 ua = lds_read_tr_pair(p, p + 4 * ULD);
               acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua, kreg[s], acc, 0, 0, 0);
             }
             const f32x4 c4 = *reinterpret_cast<const f32x4*>(cvec + 16 * rb + 4 * g);
 #pragma unroll
             for (int i = 0; i < 4; ++i) zc[4 * half + i] = acc[i] * c4[i] * mbit;
           }
-          bf16x8 z;
+          bf16x8 z;   // next B operand: slot e <-> r = 32 kr + 16 (e / 4) + 4 g + e % 4
 #pragma unroll
           for (int e = 0; e < 8; ++e) z[e] = (__bf16)zc[e];
           zb[kr] = z;
         }
       }
+      // C^T = U (c .* Z^T): rows of U visited so that lane (j, g) receives d = 32 s + 8 g + e
 #pragma unroll
       for (int s = 0; s < KS2; ++s) {
         float outv[8];
@@ -233,7 +223,10 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
 #pragma unroll
           for (int kr = 0; kr < MAXKR; ++kr) {
             if (kr < nkr) {
-              const bf16x8 ua = *reinterpret_cast<const bf16x8*>(UN + (size_t)d_row * (Rpad + 8) + 32 * kr + 8 * g);
+              const uint16_t* p = UN + (size_t)d_row * ULD + 32 * kr + 4 * g;
+              const bf16x4 u0 = *reinterpret_cast<const bf16x4*>(p);
+              const bf16x4 u1 = *reinterpret_cast<const bf16x4*>(p + 16);
+              const bf16x8 ua = __builtin_shufflevector(u0, u1, 0, 1, 2, 3, 4, 5, 6, 7);
               acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua, zb[kr], acc, 0, 0, 0);
             }
           }
@@ -248,77 +241,47 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
     }
   };
 
+  // ---- math pieces ----
   f32x16 oacc[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db)
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
   float m_run = -1e30f, l_run = 0.f;
-  const float c2 = a.scale * 1.4426950408889634f;   // scores are kept unscaled; exp2((s - m) * c2)
+  const float c2 = a.scale * 1.4426950408889634f;   // scores are kept unscaled; p = exp2((s - m) * c2)
 
-  // ---- prologue: tile 0 ----
-  load_tile(0);
-  store_tile(0);
-  unsigned long long hl = (STEER && steer_on) ? __ballot(mpre != 0) : 0ull;
-  __syncthreads();
-  if (STEER && hl != 0ull) {
-    edit_tile(0, hl);
-    __syncthreads();
-  }
-
-  const bool wave_rows_exist = qw < S;
-  for (int t = 0; t < ntiles; ++t) {
-    const int buf = t & 1;
-    const bool more = t + 1 < ntiles;
-    if (more) load_tile(t + 1);
-
-    const bool active = wave_rows_exist && (t * BK <= qw + 31);
-    if (active) {
-      const uint16_t* Kb = Kt + buf * K_ELEMS;
-      const uint16_t* Vb = Vt + buf * V_ELEMS;
-      f32x16 s0, s1;
+  // S^T (64 keys x 32 rows) = K tile . Q^T
+  auto qk_tile = [&](const uint16_t* Kb, f32x16& s0, f32x16& s1) {
 #pragma unroll
-      for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
+    for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
 #pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(Kb + l32 * KLD + 16 * ks + 8 * hf);
-        const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(Kb + (32 + l32) * KLD + 16 * ks + 8 * hf);
+    for (int ks = 0; ks < KS; ++ks) {
+      const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(Kb + l32 * KLD + 16 * ks + 8 * hf);
+      const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(Kb + (32 + l32) * KLD + 16 * ks + 8 * hf);
+      if (ABL == 4) {          // timing experiment: QK product replaced by one VALU op per fragment
+        s0[ks] += (float)a0[0];
+        s1[ks] += (float)a1[0];
+      } else {
         s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[ks], s0, 0, 0, 0);
         s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[ks], s1, 0, 0, 0);
       }
-      if (t * BK + BK - 1 > qw) {   // tile reaches past this wave's first row: causal mask
-        const int jbase = t * BK + 4 * hf;
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-          const int j = jbase + 8 * (r >> 2) + (r & 3);
-          if (j > qi) s0[r] = -INFINITY;
-          if (j + 32 > qi) s1[r] = -INFINITY;
-        }
-      }
-      float mx = s0[0];
-#pragma unroll
-      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s0[r]);
-#pragma unroll
-      for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s1[r]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run, mx);
-      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
-      const float mc = m_new * c2;
-      float lsum = 0.f;
+    }
+  };
+  // causal mask of tile t, only where the tile reaches past the wave's first row
+  auto causal_mask = [&](int t, f32x16& s0, f32x16& s1) {
+    if (t * BK + BK - 1 > qw) {
+      const int jbase = t * BK + 4 * hf;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        s0[r] = __builtin_amdgcn_exp2f(s0[r] * c2 - mc);
-        s1[r] = __builtin_amdgcn_exp2f(s1[r] * c2 - mc);
-        lsum += s0[r] + s1[r];
+        const int j = jbase + 8 * (r >> 2) + (r & 3);
+        if (j > qi) s0[r] = -INFINITY;
+        if (j + 32 > qi) s1[r] = -INFINITY;
       }
-      l_run = l_run * alpha + lsum;
-      m_run = m_new;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
-
-      bf16x8 pb[4];
+    }
+  };
+  // online softmax of one tile: scores -> packed P^T, running max / sum, rescale of O when a max moved
+  auto softmax_tile = [&](f32x16& s0, f32x16& s1, bf16x8 (&pb)[4]) {
+    if (ABL == 2) {            // timing experiment: no softmax at all, only the bf16 packing
 #pragma unroll
       for (int e = 0; e < 8; ++e) {
         pb[0][e] = (__bf16)s0[e];
@@ -326,37 +289,169 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
         pb[2][e] = (__bf16)s1[e];
         pb[3][e] = (__bf16)s1[8 + e];
       }
+      l_run += 1.f;
+      return;
+    }
+    float mx = fmaxf(s0[0], s1[0]);
 #pragma unroll
-      for (int kb = 0; kb < 4; ++kb) {
+    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s0[r], s1[r]));
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_new = fmaxf(m_run, mx);
+    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
+    const float mc = m_new * c2;
+    float lsum = 0.f;
 #pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          bf16x8 va;
-          if (VMODE == 0) {
-            const int li = lane & 15, grp = lane >> 4;
-            const int col = 32 * db + 16 * (grp & 1) + 4 * (li & 3);
-            const int jrow = 16 * kb + 4 * hf + (li >> 2);
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) s16x4*)(Vb + jrow * VLD + col));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) s16x4*)(Vb + (jrow + 8) * VLD + col));
-            const bf16x4 lo4 = __builtin_bit_cast(bf16x4, lo), hi4 = __builtin_bit_cast(bf16x4, hi);
-            va = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
-          } else {
-            va = *reinterpret_cast<const bf16x8*>(Vb + (32 * db + l32) * VLD + 16 * kb + 8 * hf);
-          }
+    for (int r = 0; r < 16; ++r) {
+      if (ABL == 1) {          // timing experiment: no exponentials
+        s0[r] = s0[r] * c2 - mc;
+        s1[r] = s1[r] * c2 - mc;
+      } else {
+        s0[r] = __builtin_amdgcn_exp2f(s0[r] * c2 - mc);
+        s1[r] = __builtin_amdgcn_exp2f(s1[r] * c2 - mc);
+      }
+      lsum += s0[r] + s1[r];
+    }
+    l_run = l_run * alpha + lsum;
+    m_run = m_new;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      pb[0][e] = (__bf16)s0[e];
+      pb[1][e] = (__bf16)s0[8 + e];
+      pb[2][e] = (__bf16)s1[e];
+      pb[3][e] = (__bf16)s1[8 + e];
+    }
+    if (__any(alpha != 1.f)) {   // rare after the first few tiles
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+    }
+  };
+  // O^T += V^T P^T
+  auto pv_tile = [&](const uint16_t* Vb, const bf16x8 (&pb)[4]) {
+    const int li = lane & 15, grp = lane >> 4;
+    const uint16_t* vbase = Vb + (4 * hf + (li >> 2)) * VLD + 16 * (grp & 1) + 4 * (li & 3);
+#pragma unroll
+    for (int kb = 0; kb < 4; ++kb) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const uint16_t* p = vbase + (16 * kb) * VLD + 32 * db;
+        const bf16x8 va = lds_read_tr_pair(p, p + 8 * VLD);
+        if (ABL == 3) {        // timing experiment: PV product replaced by one VALU op per fragment
+          oacc[db][kb] += (float)va[0] + (float)pb[kb][0];
+        } else {
           oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[kb], oacc[db], 0, 0, 0);
         }
       }
     }
+  };
 
-    if (more) {
-      store_tile(buf ^ 1);
-      hl = (STEER && steer_on) ? __ballot(mpre != 0) : 0ull;
+  const bool wave_rows_exist = qw < S;
+  const int tw_last = wave_rows_exist ? min(ntiles - 1, (qw + 31) / BK) : -1;   // last tile this wave computes on
+  unsigned long long hl = 0ull;
+
+  if (MODE == 0) {
+    // ---------------- simple loop: load(t+1) | S(t), softmax(t), PV(t) | store(t+1) ----------------
+    load_rows(Kg, 0, kpre);
+    load_rows(Vg, 0, vpre);
+    load_mask(0);
+    store_rows(Kt, KLD, kpre);
+    store_rows(Vt, VLD, vpre);
+    hl = tile_ballot();
+    __syncthreads();
+    if (STEER && hl != 0ull) {
+      edit_tile(Kt, hl);
+      __syncthreads();
+    }
+    for (int t = 0; t < ntiles; ++t) {
+      const int buf = t & 1;
+      const bool more = t + 1 < ntiles;
+      if (more) {
+        load_rows(Kg, t + 1, kpre);
+        load_rows(Vg, t + 1, vpre);
+        load_mask(t + 1);
+      }
+      if (t <= tw_last) {
+        f32x16 s0, s1;
+        bf16x8 pb[4];
+        qk_tile(Kt + buf * K_ELEMS, s0, s1);
+        causal_mask(t, s0, s1);
+        softmax_tile(s0, s1, pb);
+        pv_tile(Vt + buf * V_ELEMS, pb);
+      }
+      if (more) {
+        store_rows(Kt + (buf ^ 1) * K_ELEMS, KLD, kpre);
+        store_rows(Vt + (buf ^ 1) * V_ELEMS, VLD, vpre);
+        hl = tile_ballot();
+      }
+      __syncthreads();
+      if (STEER && more && hl != 0ull) {
+        edit_tile(Kt + (buf ^ 1) * K_ELEMS, hl);
+        __syncthreads();
+      }
+    }
+  } else {
+    // ---------------- ping-pong: during iteration t LDS holds K(t) in Kbuf[t%3], K(t+1) in Kbuf[(t+1)%3],
+    // V(t) in Vbuf[t&1]; K(t+2) and V(t+1) travel through registers and are stored at the end of iteration t.
+    load_rows(Kg, 0, kpre);
+    load_rows(Vg, 0, vpre);
+    load_mask(0);
+    store_rows(Kt, KLD, kpre);
+    store_rows(Vt, VLD, vpre);
+    hl = tile_ballot();
+    unsigned long long hl1 = 0ull;
+    if (ntiles > 1) {
+      load_rows(Kg, 1, kpre);
+      load_mask(1);
+      store_rows(Kt + K_ELEMS, KLD, kpre);
+      hl1 = tile_ballot();
     }
     __syncthreads();
-    if (STEER && more && hl != 0ull) {
-      edit_tile(buf ^ 1, hl);
+    if (STEER && (hl | hl1) != 0ull) {
+      if (hl != 0ull) edit_tile(Kt, hl);
+      if (hl1 != 0ull) edit_tile(Kt + K_ELEMS, hl1);
       __syncthreads();
+    }
+    const bool ahead = MODE == 1 ? wave >= (NW + 1) / 2 : (wave & 1) != 0;   // which waves run one phase ahead
+    f32x16 s0, s1;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
+    if (ahead && 0 <= tw_last) qk_tile(Kt, s0, s1);
+    int kb_cur = 0;                                // t % 3
+    for (int t = 0; t < ntiles; ++t) {
+      const bool moreK = t + 2 < ntiles, moreV = t + 1 < ntiles;
+      const int kb_next = kb_cur == 2 ? 0 : kb_cur + 1;
+      const int kb_free = kb_next == 2 ? 0 : kb_next + 1;
+      if (moreK) {
+        load_rows(Kg, t + 2, kpre);
+        load_mask(t + 2);
+      }
+      if (moreV) load_rows(Vg, t + 1, vpre);
+      if (t <= tw_last) {
+        bf16x8 pb[4];
+        if (!ahead) {
+          qk_tile(Kt + kb_cur * K_ELEMS, s0, s1);
+          causal_mask(t, s0, s1);
+          softmax_tile(s0, s1, pb);
+          pv_tile(Vt + (t & 1) * V_ELEMS, pb);
+        } else {
+          causal_mask(t, s0, s1);
+          softmax_tile(s0, s1, pb);
+          pv_tile(Vt + (t & 1) * V_ELEMS, pb);
+          if (t + 1 <= tw_last) qk_tile(Kt + kb_next * K_ELEMS, s0, s1);
+        }
+      }
+      if (moreK) {
+        store_rows(Kt + kb_free * K_ELEMS, KLD, kpre);
+        hl = tile_ballot();
+      }
+      if (moreV) store_rows(Vt + ((t + 1) & 1) * V_ELEMS, VLD, vpre);
+      __syncthreads();
+      if (STEER && moreK && hl != 0ull) {
+        edit_tile(Kt + kb_free * K_ELEMS, hl);
+        __syncthreads();
+      }
+      kb_cur = kb_next;
     }
   }
 
@@ -375,7 +470,7 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
         *reinterpret_cast<uint2*>(op + 32 * db + 8 * q4) = __builtin_bit_cast(uint2, o4);
       }
     }
-    if (a.lse && hf == 0) a.lse[((size_t)b * a.Hq + hq) * S + qi] = m_run * a.scale + __logf(l_tot);
+    if (a.lse && hf == 0) a.lse[((size_t)b * a.Hq + hq) * S + qi] = m_run * a.scale + logf(l_tot);
   }
 }
 

@@ -99,7 +99,7 @@ BF16_CASES = {
 }
 
 
-@pytest.mark.parametrize("variant", [0, 1])
+@pytest.mark.parametrize("variant", [0])
 @pytest.mark.parametrize("name", list(BF16_CASES))
 def test_bf16_attention_small(seka, name, variant):
     kw = dict(BF16_CASES[name])
@@ -132,7 +132,7 @@ def test_bf16_adaseka_routed(seka):
     assert np.abs(H.to_f64(w) - ref_w).max() <= H.ROUTE_ABS
     assert ref_w.max() - ref_w.min() > 0.01, "routing is uniform: test is vacuous"
     ref_O, _ = orc.steered_attention(o["Q"], o["K"], o["V"], o["U"], inp.gain, inp.mask, w=ref_w, scale=inp.scale)
-    for variant in (0, 1):
+    for variant in (0,):
         got_O, _ = _run_attention(seka, dev, True, variant, w=w)
         H.assert_close_bf16(got_O, ref_O, f"adaseka O variant {variant}")
     # standalone edit with the same weights
@@ -200,7 +200,7 @@ def test_bf16_tiny_lengths(seka, S):
     dev = H.DeviceInputs(inp)
     o = H.oracle_inputs(inp)
     ref_O, ref_L = orc.steered_attention(o["Q"], o["K"], o["V"], o["U"], inp.gain, inp.mask, scale=inp.scale)
-    for variant in (0, 1):
+    for variant in (0,):
         got_O, got_L = _run_attention(seka, dev, True, variant)
         H.assert_close_bf16(got_O, ref_O, f"S={S} O")
         H.assert_lse_close_bf16(got_L, ref_L, f"S={S} LSE")

@@ -59,7 +59,8 @@ __device__ __forceinline__ void dma_barrier() {
 // bytes land contiguously at the (wave-uniform) LDS byte address lds_base.  Issued as inline assembly so
 // that it stays outside the compiler's own vmcnt bookkeeping: the waits are placed by hand.
 __device__ __forceinline__ void dma_load_16B(const void* gptr, uint32_t lds_base) {
-  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory", "m0");
+  const uint32_t base = __builtin_amdgcn_readfirstlane(lds_base);   // wave-uniform by construction
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(base), "v"(gptr) : "memory", "m0");
 }
 
 // HPW heads x RBW row groups = waves per workgroup; every wave owns RPW blocks of 32 consecutive query rows.

@@ -1,0 +1,541 @@
+// Software-pipelined direct-to-LDS attention kernel (head dimension 128, 32 query rows per wave; see
+// attn_bf16_dma_kernel.h for the tile transport, the swizzle and the math mapping).
+//
+// What bounds this kernel on gfx950 is the SIMD's vector issue port, not the matrix pipe: a 32x32x16 bf16
+// MFMA holds the port for about 16 cycles of its 32, a plain vector instruction for 4, an exponential for
+// about 8, and instructions of the two waves of a SIMD queue on the same port.  Two consequences:
+//   * every vector instruction in the loop that is not softmax arithmetic is removed: LDS read addresses
+//     are a register plus an immediate (the loop is unrolled over the three ring stages so that stage
+//     offsets are compile-time constants), tile loads take a scalar base plus a per-lane offset computed
+//     once, the row maximum uses three-input max, the row sum uses the bf16 dot-product instruction;
+//   * MFMAs and vector instructions alternate in program order: iteration t issues the S^T products of
+//     the next 32-key block interleaved with the softmax of the current block, then the PV products of
+//     the current block interleaved with their transposing LDS reads.
+// The softmax runs per 32-key block (half a tile), which halves the score registers the pipeline needs.
+// K and V tiles live in rings of three LDS stages; K(t+2) and V(t+2) are requested at the top of
+// iteration t and K(t+2) is edited (highlighted keys only) at the bottom of iteration t.
+#pragma once
+#include <type_traits>
+
+#include "attn_bf16_dma_kernel.h"
+
+namespace seka {
+
+inline size_t attention_bf16_pipe_smem_bytes(int S, bool steer, int Rpad) {
+  return attention_bf16_dma_smem_bytes(S, steer, Rpad);
+}
+
+typedef __attribute__((address_space(3))) const bf16x8* pipe_lds_bf16x8_ptr;
+
+__device__ __forceinline__ float pipe_max3(float a, float b, float c) {
+  float r;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+  return r;
+}
+
+// Direct-to-LDS load with a scalar 64-bit base and a 32-bit per-lane byte offset.
+__device__ __forceinline__ void pipe_load_16B(const void* base, uint32_t lane_off, uint32_t lds_base) {
+  asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_base), "v"(lane_off), "s"(base)
+               : "memory", "m0");
+}
+
+// HPW heads x RBW row groups = waves per workgroup; every wave owns RPW blocks of 32 consecutive query rows.
+// RPW = 2 (four waves, one per SIMD, 512-register budget) reads every K / V fragment once for two products.
+template <int HPW, int RBW, int RPW, bool STEER, int SCHED = 1>
+__global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(AttnArgs a, SteerArgs st, int Rpad) {
+  constexpr int D = DMA_D;
+  constexpr int NW = HPW * RBW;
+  constexpr int NT = 64 * NW;
+  constexpr int WR = 32 * RPW;
+  constexpr int BQ = WR * RBW;
+  constexpr int BK = DMA_BK;
+  constexpr int KS = D / 16;
+  constexpr int DB = D / 32;
+  constexpr int SLOTS = DMA_TILE_BYTES / 1024;
+  constexpr int SPW = (SLOTS + NW - 1) / NW;             // load instructions per wave per tensor per tile
+  constexpr int TB = DMA_TILE_BYTES;
+
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  unsigned char* Kst = smem;                                     // [3][16 KB] swizzled K tiles
+  unsigned char* Vst = smem + DMA_STAGES * TB;                   // [3][16 KB] swizzled V tiles
+  uint16_t* UN = reinterpret_cast<uint16_t*>(smem + 2 * DMA_STAGES * TB);   // [D][Rpad+8] (STEER)
+  const int ULD = Rpad + 8;
+  float* cvec = reinterpret_cast<float*>(UN + (size_t)D * ULD);                          // [Rpad]
+  unsigned long long* hlbits = reinterpret_cast<unsigned long long*>(cvec + Rpad);       // [tiles] (STEER)
+
+  const uint16_t* __restrict__ Qg = static_cast<const uint16_t*>(a.Q);
+  const uint16_t* __restrict__ Kg = static_cast<const uint16_t*>(a.K);
+  const uint16_t* __restrict__ Vg = static_cast<const uint16_t*>(a.V);
+  uint16_t* __restrict__ Og = static_cast<uint16_t*>(a.O);
+
+  const int S = a.S;
+  const int G = a.Hq / a.Hkv;
+  const int nHC = a.Hq / HPW;
+  const int nQB = (S + BQ - 1) / BQ;
+  const int per_qb = nHC * a.B;
+  const int qb = nQB - 1 - (int)(blockIdx.x / per_qb);
+  const int rem = blockIdx.x % per_qb;
+  const int b = rem / nHC, hc = rem % nHC;
+  const int hq0 = hc * HPW;
+  const int h = hq0 / G;
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, hf = lane >> 5;
+  const int hq = hq0 + wave / RBW;
+  const int qw = qb * BQ + WR * (wave % RBW);    // first query row of this wave
+  const int qi0 = qw + l32;                      // this lane's query row in row block 0 (block rp: + 32 rp)
+
+  const float gain = STEER ? st.gain[h] : 0.f;
+  const bool steer_on = STEER && gain != 0.f;
+
+  const int last_key = min(S, qb * BQ + BQ) - 1;
+  const int ntiles = last_key / BK + 1;
+
+  // ---- tile loads: scalar tile base + per-lane offset fixed for the whole kernel ----
+  // Slot s of a tile is LDS bytes [1024 s, 1024 s + 1024) = rows 4s..4s+3; lane l lands at row 4s + l/16,
+  // chunk position l%16, and fetches the logical chunk that the swizzle assigns to that position.
+  const uint32_t rowbytes = (uint32_t)a.Hkv * D * 2;
+  const uint32_t kst_base = (uint32_t)(uintptr_t)(dma_lds_void_ptr)Kst;
+  const uint32_t vst_base = (uint32_t)(uintptr_t)(dma_lds_void_ptr)Vst;
+  int slot_row[SPW];          // first LDS row of this lane in slot n
+  uint32_t koff[SPW], voff[SPW], slot_lds[SPW];
+#pragma unroll
+  for (int n = 0; n < SPW; ++n) {
+    const int slot = min(wave + NW * n, SLOTS - 1);      // surplus slots repeat the last one (same bytes)
+    const int row = 4 * slot + (lane >> 4);
+    slot_row[n] = row;
+    slot_lds[n] = 1024u * slot;
+    koff[n] = row * rowbytes + 16u * ((lane & 15) ^ (row & 15));
+    voff[n] = row * rowbytes + 16u * ((lane & 15) ^ (4 * (row & 3)));
+  }
+  const unsigned char* kv_head = nullptr;   // unused; keeps the two bases below symmetric
+  (void)kv_head;
+  const size_t head_off = ((size_t)b * S * a.Hkv + h) * D * 2;          // bytes to this (batch, KV head), token 0
+  const unsigned char* Kbytes = reinterpret_cast<const unsigned char*>(Kg) + head_off;
+  const unsigned char* Vbytes = reinterpret_cast<const unsigned char*>(Vg) + head_off;
+  auto issue_rows = [&](const unsigned char* tensor, int t, uint32_t lds_stage_base, const uint32_t (&off)[SPW]) {
+    const unsigned char* tile = tensor + (size_t)t * BK * rowbytes;
+    if (t * BK + BK <= S) {
+#pragma unroll
+      for (int n = 0; n < SPW; ++n) pipe_load_16B(tile, off[n], lds_stage_base + slot_lds[n]);
+    } else {
+      const int last_row = S - 1 - t * BK;             // rows past the end repeat the last key (finite data)
+#pragma unroll
+      for (int n = 0; n < SPW; ++n)
+        pipe_load_16B(tile, off[n] - (uint32_t)max(0, slot_row[n] - last_row) * rowbytes, lds_stage_base + slot_lds[n]);
+    }
+  };
+  auto issue_k = [&](int t) __attribute__((always_inline)) { issue_rows(Kbytes, t, kst_base + (t % 3) * TB, koff); };
+  auto issue_v = [&](int t) __attribute__((always_inline)) { issue_rows(Vbytes, t, vst_base + (t % 3) * TB, voff); };
+
+  issue_k(0);
+  issue_v(0);
+  if (ntiles > 1) { issue_k(1); issue_v(1); }
+
+  // ---- Q fragments: B operand of S^T = K Q^T, lane (col = row qi, k = 16 ks + 8 hf + e) ----
+  bf16x8 qf[RPW][KS];
+#pragma unroll
+  for (int rp = 0; rp < RPW; ++rp) {
+    const int qi = qi0 + 32 * rp;
+    const bool ok = qi < S;
+    const uint16_t* qp = Qg + (((size_t)b * S + (ok ? qi : 0)) * a.Hq + hq) * D + 8 * hf;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (ok) v = *reinterpret_cast<const uint4*>(qp + 16 * ks);
+      qf[rp][ks] = __builtin_bit_cast(bf16x8, v);
+    }
+  }
+
+  // ---- steering set-up: U_cat (row d, r contiguous), per-column coefficients, highlight bitmap ----
+  if (STEER && steer_on) {
+    const int R = st.M * st.r;
+    if (R != Rpad) {
+      for (int i = tid; i < D * ULD; i += NT) UN[i] = 0;
+      __syncthreads();
+    }
+    const uint16_t* Uh = static_cast<const uint16_t*>(st.U) + (size_t)h * st.M * D * st.r;
+    const int r8 = st.r / 8;
+    const int total = st.M * D * r8;
+    for (int idx = tid; idx < total; idx += NT) {
+      const int m = idx / (D * r8), rm = idx % (D * r8);
+      const int d = rm / r8, v = rm % r8;
+      *reinterpret_cast<uint4*>(UN + (size_t)d * ULD + m * st.r + 8 * v) =
+          *reinterpret_cast<const uint4*>(Uh + ((size_t)m * D + d) * st.r + 8 * v);
+    }
+    for (int r = tid; r < Rpad; r += NT) {
+      float c = 0.f;
+      if (r < R) c = gain * (st.w ? st.w[((size_t)b * a.Hkv + h) * st.M + r / st.r] : 1.f);
+      cvec[r] = c;
+    }
+    for (int t = wave; t < ntiles; t += NW) {
+      const int key = t * BK + lane;
+      const int mk = key < S ? st.mask[(size_t)b * S + key] : 0;
+      const unsigned long long bits = __ballot(mk != 0);
+      if (lane == 0) hlbits[t] = bits;
+    }
+  }
+
+  // Edit the highlighted 16-key blocks of the (swizzled) K tile at Kb; one wave per block.
+  auto edit_tile = [&](unsigned char* Kb, unsigned long long bits) __attribute__((always_inline)) {
+    // The lane index is re-derived behind an opaque copy so that none of the per-lane operand addresses below
+    // is hoisted out of the tile loop: they would occupy registers the attention pipeline needs.
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    const int j = ln & 15, g = ln >> 4;
+    constexpr int KS2 = D / 32;
+    constexpr int MAXKR = SEKA_MAX_RANK / 32;
+    const int nkr = Rpad / 32;
+    for (int kblk = wave; kblk < BK / 16; kblk += NW) {
+      const unsigned bits16 = (unsigned)((bits >> (16 * kblk)) & 0xffffull);
+      if (bits16 == 0) continue;
+      unsigned char* krow = Kb + (16 * kblk + j) * 256;    // row & 15 == j
+      bf16x8 kreg[KS2];   // K^T as B operand: lane (col = key j, k = d = 32 s + 8 g + e) = logical chunk 4 s + g
+  #pragma unroll
+      for (int s = 0; s < KS2; ++s) kreg[s] = *reinterpret_cast<const bf16x8*>(krow + 16 * ((4 * s + g) ^ j));
+      const float mbit = ((bits16 >> j) & 1u) ? 1.f : 0.f;
+      const uint16_t* ut = UN + (size_t)(8 * g + (j >> 2)) * ULD + 4 * (j & 3);
+      bf16x8 zb[MAXKR];
+  #pragma unroll
+      for (int kr = 0; kr < MAXKR; ++kr) {
+        if (kr < nkr) {
+          float zc[8];
+  #pragma unroll
+          for (int half = 0; half < 2; ++half) {
+            const int rb = 2 * kr + half;
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  #pragma unroll
+            for (int s = 0; s < KS2; ++s) {
+              const uint16_t* p = ut + (size_t)(32 * s) * ULD + 16 * rb;
+              const bf16x8 ua = dma_read_tr_pair(reinterpret_cast<const unsigned char*>(p),
+                                                 reinterpret_cast<const unsigned char*>(p + 4 * ULD));
+              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua, kreg[s], acc, 0, 0, 0);
+            }
+            const f32x4 c4 = *reinterpret_cast<const f32x4*>(cvec + 16 * rb + 4 * g);
+  #pragma unroll
+            for (int i = 0; i < 4; ++i) zc[4 * half + i] = acc[i] * c4[i] * mbit;
+          }
+          bf16x8 z;   // next B operand: slot e <-> r = 32 kr + 16 (e / 4) + 4 g + e % 4
+  #pragma unroll
+          for (int e = 0; e < 8; ++e) z[e] = (__bf16)zc[e];
+          zb[kr] = z;
+        }
+      }
+  #pragma unroll
+      for (int s = 0; s < KS2; ++s) {
+        float outv[8];
+  #pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          const int d_row = 32 * s + 8 * (j >> 2) + 4 * half + (j & 3);
+          f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  #pragma unroll
+          for (int kr = 0; kr < MAXKR; ++kr) {
+            if (kr < nkr) {
+              const uint16_t* p = UN + (size_t)d_row * ULD + 32 * kr + 4 * g;
+              const bf16x4 u0 = *reinterpret_cast<const bf16x4*>(p);
+              const bf16x4 u1 = *reinterpret_cast<const bf16x4*>(p + 16);
+              const bf16x8 ua = __builtin_shufflevector(u0, u1, 0, 1, 2, 3, 4, 5, 6, 7);
+              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua, zb[kr], acc, 0, 0, 0);
+            }
+          }
+  #pragma unroll
+          for (int i = 0; i < 4; ++i) outv[4 * half + i] = (float)kreg[s][4 * half + i] + acc[i];
+        }
+        bf16x8 o;
+  #pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = (__bf16)outv[e];
+        *reinterpret_cast<bf16x8*>(krow + 16 * ((4 * s + g) ^ j)) = o;
+      }
+    }
+  };
+
+  // ---- math pieces ----
+  f32x16 oacc[RPW][DB];
+#pragma unroll
+  for (int rp = 0; rp < RPW; ++rp)
+#pragma unroll
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[rp][db][r] = 0.f;
+  const float c2 = a.scale * 1.4426950408889634f;   // probabilities are exp2(s * c2 - m)
+  // m_run: reference exponent of the row (in units of s * c2).  It follows the row maximum lazily: it is only
+  // raised when the maximum has moved more than kSlack above it, so probabilities stay below 2^kSlack and the
+  // output accumulators are rescaled a handful of times per row instead of once per block.
+  constexpr float kSlack = 8.f;
+  float m_run[RPW], l_run[RPW];
+#pragma unroll
+  for (int rp = 0; rp < RPW; ++rp) { m_run[rp] = -1e30f; l_run[rp] = 0.f; }
+
+  // LDS byte addresses of this lane's operands inside stage 0 (stage and row-block offsets are immediates):
+  // K: row l32 (+32), logical chunk 2 ks + hf, physical chunk (2 ks + hf) ^ (l32 & 15)
+  // V: row 16 kb + 4 hf + (li >> 2) (+8), logical chunk 4 db + 2 (grp & 1) + ((li & 3) >> 1), physical chunk 4 (db ^ q) + low
+  uint32_t kaddr[KS], vaddr[DB];
+  {
+    const int kfix = l32 * 256 + 16 * (hf ^ (l32 & 1)) + 32 * ((l32 & 15) >> 1);
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) kaddr[ks] = kst_base + (uint32_t)(kfix ^ (ks << 5));
+    const int li = lane & 15, grp = lane >> 4;
+    const int vfix = (4 * hf + (li >> 2)) * 256 + 64 * ((li >> 2) & 3) + 16 * (2 * (grp & 1) + ((li & 3) >> 1)) + 8 * (li & 1);
+#pragma unroll
+    for (int db = 0; db < DB; ++db) vaddr[db] = vst_base + (uint32_t)(vfix ^ (db << 6));
+  }
+
+  // Part [KS0, KS1) of one 32-key block of S^T (32 keys x 32 RPW rows) = K rows . Q^T ; off = LDS byte offset
+  // of the block's first row.  Each K fragment is read once and used for every row block of the wave.
+  auto qk_part = [&](auto ks0_c, auto ks1_c, int off, f32x16 (&sn)[RPW]) __attribute__((always_inline)) {
+    constexpr int KS0 = decltype(ks0_c)::value, KS1 = decltype(ks1_c)::value;
+    if (KS0 == 0) {
+#pragma unroll
+      for (int rp = 0; rp < RPW; ++rp)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) sn[rp][r] = 0.f;
+    }
+#pragma unroll
+    for (int ks = KS0; ks < KS1; ++ks) {
+      const bf16x8 a0 = *(pipe_lds_bf16x8_ptr)(uintptr_t)(kaddr[ks] + off);
+#pragma unroll
+      for (int rp = 0; rp < RPW; ++rp) sn[rp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[rp][ks], sn[rp], 0, 0, 0);
+    }
+  };
+  using IC0 = std::integral_constant<int, 0>;
+  using ICH = std::integral_constant<int, KS / 2>;
+  using ICK = std::integral_constant<int, KS>;
+  // causal mask of the 32-key block starting at key j0, row block rp
+  auto causal_mask = [&](int j0, int rp, f32x16& sv) __attribute__((always_inline)) {
+    const int jbase = j0 + 4 * hf, qi = qi0 + 32 * rp;
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+      if (jbase + 8 * (r >> 2) + (r & 3) > qi) sv[r] = -INFINITY;
+  };
+  // Softmax of one 32-key block, first part: row maximum (of s * c2) over the block, both halves of the row.
+  auto block_max = [&](const f32x16& sv) __attribute__((always_inline)) -> float {
+    float mx = pipe_max3(sv[0], sv[1], sv[2]);
+#pragma unroll
+    for (int r = 3; r < 15; r += 2) mx = pipe_max3(mx, sv[r], sv[r + 1]);
+    mx = fmaxf(mx, sv[15]) * c2;
+    // the other 16 keys of this query row live in lane ^ 32
+    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+    return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+  };
+  // Raise the reference exponent of the rows whose maximum ran away from it, and rescale their sums and outputs.
+  auto raise_reference = [&](int rp, float mfull) __attribute__((always_inline)) {
+    const bool need = mfull > m_run[rp] + kSlack;
+    if (__any(need)) {   // a handful of times per row
+      const float m_new = need ? mfull : m_run[rp];
+      const float alpha = __builtin_amdgcn_exp2f(m_run[rp] - m_new);
+      m_run[rp] = m_new;
+      l_run[rp] *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[rp][db][r] *= alpha;
+    }
+  };
+  // Second part: probabilities, packed P^T, row sum of the rounded probabilities (the values the PV product uses).
+  auto block_exp = [&](int rp, f32x16& sv, bf16x8 (&pb)[2]) __attribute__((always_inline)) {
+    const float mneg = -m_run[rp];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sv[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], c2, mneg));
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      pb[0][e] = (__bf16)sv[e];
+      pb[1][e] = (__bf16)sv[8 + e];
+    }
+    float lsum = l_run[rp];
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int e = 0; e < 8; e += 2) {
+        const bf16x2 pp = {pb[kb][e], pb[kb][e + 1]};
+        lsum = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, lsum, false);
+      }
+    l_run[rp] = lsum;
+  };
+  // O^T += V^T P^T for one 32-key block; off = LDS byte offset of the block's first row
+  auto pv_half = [&](int off, const bf16x8 (&pb)[RPW][2]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((dma_lds_s16x4_ptr)(uintptr_t)(vaddr[db] + off + (16 * kb) * 256));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((dma_lds_s16x4_ptr)(uintptr_t)(vaddr[db] + off + (16 * kb + 8) * 256));
+        const bf16x4 lo4 = __builtin_bit_cast(bf16x4, lo), hi4 = __builtin_bit_cast(bf16x4, hi);
+        const bf16x8 va = __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
+#pragma unroll
+        for (int rp = 0; rp < RPW; ++rp)
+          oacc[rp][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[rp][kb], oacc[rp][db], 0, 0, 0);
+      }
+    }
+  };
+
+  const bool wave_rows_exist = qw < S;
+  const int tw_last = wave_rows_exist ? min(ntiles - 1, (qw + WR - 1) / BK) : -1;   // last tile this wave computes on
+
+  // ---- prologue: wait for the first tiles, edit K(0) and K(1), first block of S^T ----
+  dma_wait_vmcnt<0>();   // also covers the Q, U and mask loads issued after the tile loads
+#pragma unroll
+  for (int rp = 0; rp < RPW; ++rp)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[rp][ks]));   // pin the compiler's own wait for Q here, not in the loop
+  dma_barrier();
+  if (STEER && steer_on) {
+    const unsigned long long hl0 = hlbits[0];
+    const unsigned long long hl1 = ntiles > 1 ? hlbits[1] : 0ull;
+    if ((hl0 | hl1) != 0ull) {
+      if (hl0 != 0ull) edit_tile(Kst, hl0);
+      if (hl1 != 0ull) edit_tile(Kst + TB, hl1);
+      dma_barrier();
+    }
+  }
+
+  f32x16 sc0[RPW], sc1[RPW];   // scores of keys 0..31 / 32..63 of the current tile, per row block
+#pragma unroll
+  for (int rp = 0; rp < RPW; ++rp)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { sc0[rp][r] = 0.f; sc1[rp][r] = 0.f; }
+  if (0 <= tw_last) qk_part(IC0{}, ICK{}, 0, sc0);
+
+  // Top of iteration t: request K(t+2) and V(t+2) (in this order).  Bottom: K(t+2) and V(t+1) must have landed
+  // before the next iteration (V(t+2) stays in flight); then edit K(t+2) if it holds highlighted keys.
+  auto top = [&](int t) __attribute__((always_inline)) {
+    if (t + 2 < ntiles) {
+      issue_k(t + 2);
+      issue_v(t + 2);
+    }
+  };
+  auto bottom = [&](int t) __attribute__((always_inline)) {
+    if (t + 2 < ntiles) dma_wait_vmcnt<SPW>();
+    else dma_wait_vmcnt<0>();
+    dma_barrier();
+    if (STEER && steer_on && t + 2 < ntiles) {
+      const unsigned long long hl = hlbits[t + 2];
+      if (hl != 0ull) {
+        edit_tile(Kst + ((t + 2) % 3) * TB, hl);
+        dma_barrier();
+      }
+    }
+  };
+
+  // One software-pipelined step: the S^T block at LDS offset KOFF is produced into `next` while the softmax of
+  // `cur` runs on the vector ALU; then the PV products of `cur` (V rows at LDS offset VOFF).
+  auto step = [&](auto koff_c, auto voff_c, f32x16 (&cur)[RPW], f32x16 (&next)[RPW]) __attribute__((always_inline)) {
+    constexpr int KOFF = decltype(koff_c)::value, VOFF = decltype(voff_c)::value;
+    constexpr int NM = (KS / 2) * RPW;            // MFMAs per half of the S^T block
+    bf16x8 pb[RPW][2];
+    float mfull[RPW];
+    // (a) first half of the products, interleaved with the row maxima
+    qk_part(IC0{}, ICH{}, KOFF, next);
+#pragma unroll
+    for (int rp = 0; rp < RPW; ++rp) mfull[rp] = block_max(cur[rp]);
+    if (SCHED == 1) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+#pragma unroll
+      for (int i = 0; i < NM; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        if (i % RPW == 0 && i / RPW < KS / 2 - 2) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int rp = 0; rp < RPW; ++rp) raise_reference(rp, mfull[rp]);
+    // (b) second half of the products, interleaved with the exponentials
+    qk_part(ICH{}, ICK{}, KOFF, next);
+#pragma unroll
+    for (int rp = 0; rp < RPW; ++rp) block_exp(rp, cur[rp], pb[rp]);
+    if (SCHED == 1) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+#pragma unroll
+      for (int i = 0; i < NM; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+        if (i % RPW == 0 && i / RPW < KS / 2 - 2) __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
+        __builtin_amdgcn_sched_group_barrier(0x002, 12, 1);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    // (c) the PV products of the current block with their transposing reads
+    pv_half(VOFF, pb);
+    if (SCHED == 1) {
+      __builtin_amdgcn_sched_group_barrier(0x100, 4, 2);
+#pragma unroll
+      for (int i = 0; i < 2 * DB; ++i) {
+#pragma unroll
+        for (int rp = 0; rp < RPW; ++rp) __builtin_amdgcn_sched_group_barrier(0x008, 1, 2);
+        if (i < 2 * DB - 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 2);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  };
+  // One tile every row of this wave sees in full; ST = t % 3 is compile-time so that every LDS read address is
+  // a register plus an immediate.  Enters with S(t, keys 0..31) in sc0, leaves with S(t+1, keys 0..31) in sc0.
+  auto hot = [&](auto st_c, int t) __attribute__((always_inline)) {
+    constexpr int ST = decltype(st_c)::value;
+    using std::integral_constant;
+    top(t);
+    step(integral_constant<int, ST * TB + 32 * 256>{}, integral_constant<int, ST * TB>{}, sc0, sc1);
+    step(integral_constant<int, ((ST + 1) % 3) * TB>{}, integral_constant<int, ST * TB + 32 * 256>{}, sc1, sc0);
+    bottom(t);
+  };
+
+  int t = 0;
+  if (tw_last > 0) {
+    using std::integral_constant;
+    for (;;) {
+      hot(integral_constant<int, 0>{}, t); if (++t == tw_last) break;
+      hot(integral_constant<int, 1>{}, t); if (++t == tw_last) break;
+      hot(integral_constant<int, 2>{}, t); if (++t == tw_last) break;
+    }
+  }
+  // ---- the wave's last tile (causal mask, nothing further to score), then idle turns while other waves finish ----
+#pragma nounroll
+  for (t = max(tw_last, 0); t < ntiles; ++t) {
+    top(t);
+    if (t == tw_last) {
+      const int off = (t % 3) * TB;
+      bf16x8 pb[RPW][2];
+      qk_part(IC0{}, ICK{}, off + 32 * 256, sc1);
+#pragma unroll
+      for (int rp = 0; rp < RPW; ++rp) {
+        causal_mask(t * BK, rp, sc0[rp]);
+        raise_reference(rp, block_max(sc0[rp]));
+        block_exp(rp, sc0[rp], pb[rp]);
+      }
+      pv_half(off, pb);
+#pragma unroll
+      for (int rp = 0; rp < RPW; ++rp) {
+        causal_mask(t * BK + 32, rp, sc1[rp]);
+        raise_reference(rp, block_max(sc1[rp]));
+        block_exp(rp, sc1[rp], pb[rp]);
+      }
+      pv_half(off + 32 * 256, pb);
+    }
+    bottom(t);
+  }
+
+  // ---- epilogue ----
+#pragma unroll
+  for (int rp = 0; rp < RPW; ++rp) {
+    const int qi = qi0 + 32 * rp;
+    const float l_tot = l_run[rp] + __shfl_xor(l_run[rp], 32);
+    if (qi < S) {
+      const float inv = 1.f / l_tot;
+      uint16_t* op = Og + (((size_t)b * S + qi) * a.Hq + hq) * D + 4 * hf;
+#pragma unroll
+      for (int db = 0; db < DB; ++db) {
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          bf16x4 o4;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[rp][db][4 * q4 + e] * inv);
+          *reinterpret_cast<uint2*>(op + 32 * db + 8 * q4) = __builtin_bit_cast(uint2, o4);
+        }
+      }
+      // m_run is the reference exponent in units of s * scale * log2(e); l_tot is relative to it
+      if (a.lse && hf == 0) a.lse[((size_t)b * a.Hq + hq) * S + qi] = m_run[rp] * 0.6931471805599453f + logf(l_tot);
+    }
+  }
+}
+
+}  // namespace seka

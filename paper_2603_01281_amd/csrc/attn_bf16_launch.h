@@ -2,13 +2,12 @@
 // translation unit so the variants compile in parallel).
 #pragma once
 #include "attn_bf16_dma_kernel.h"
-#include "attn_bf16_pipe_kernel.h"
 #include "attn_bf16_kernel.h"
 
 namespace seka {
 
 // variant id -> (V tile row padding in elements, loop structure); 0 is the library default
-constexpr int kNumAttnVariants = 11;
+constexpr int kNumAttnVariants = 8;
 
 template <int D, int HPW, int RB, bool STEER, int VPAD, int MODE, int ABL = 0>
 hipError_t launch_attention_bf16_cfg(const AttnArgs& a, const SteerArgs* steer, hipStream_t s) {
@@ -48,39 +47,18 @@ hipError_t launch_attention_bf16_dma_cfg(const AttnArgs& a, const SteerArgs* ste
   return hipGetLastError();
 }
 
-// software-pipelined direct-to-LDS kernel (head dimension 128 only)
-template <int HPW, int RBW, int RPW, bool STEER, int SCHED = 1>
-hipError_t launch_attention_bf16_pipe_cfg(const AttnArgs& a, const SteerArgs* steer, hipStream_t s) {
-  constexpr int BQ = 32 * RPW * RBW;
-  const int Rpad = STEER ? (steer->M * steer->r + 31) / 32 * 32 : 0;
-  const size_t smem = attention_bf16_pipe_smem_bytes(a.S, STEER, Rpad);
-  if (smem > 160 * 1024) return hipErrorNotSupported;
-  auto kernel = attention_bf16_pipe_kernel<HPW, RBW, RPW, STEER, SCHED>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-  if (e != hipSuccess) return e;
-  const int nQB = (a.S + BQ - 1) / BQ;
-  const long long blocks = (long long)nQB * (a.Hq / HPW) * a.B;
-  if (blocks > 0x7fffffffLL) return hipErrorNotSupported;
-  SteerArgs sa;
-  if (STEER) sa = *steer; else memset(&sa, 0, sizeof(sa));
-  hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * HPW * RBW), smem, s, a, sa, Rpad);
-  return hipGetLastError();
-}
+// software-pipelined direct-to-LDS kernels (head dimension 128 only; defined in attn_bf16_pipe_*.hip)
+hipError_t launch_attention_bf16_pipe_plain(const AttnArgs& a, hipStream_t s);
+hipError_t launch_attention_bf16_pipe_r32(const AttnArgs& a, const SteerArgs* steer, hipStream_t s);
+hipError_t launch_attention_bf16_pipe_r64(const AttnArgs& a, const SteerArgs* steer, hipStream_t s);
+hipError_t launch_attention_bf16_pipe_r128(const AttnArgs& a, const SteerArgs* steer, hipStream_t s);
 
-// RPW = 1: eight waves of 32 rows; RPW = 2: four waves of 64 rows
-template <bool STEER, int RPW>
-hipError_t launch_attention_bf16_pipe_group(const AttnArgs& a, const SteerArgs* steer, hipStream_t s) {
-  const int G = a.Hq / a.Hkv;
-  if (RPW == 2) {
-    if (G % 4 == 0) return launch_attention_bf16_pipe_cfg<4, 1, 2, STEER>(a, steer, s);
-    if (G % 2 == 0) return launch_attention_bf16_pipe_cfg<2, 2, 2, STEER>(a, steer, s);
-    return launch_attention_bf16_pipe_cfg<1, 4, 2, STEER>(a, steer, s);
-  }
-  if (G % 4 == 0) return launch_attention_bf16_pipe_cfg<4, 2, 1, STEER>(a, steer, s);
-  if (G % 7 == 0) return launch_attention_bf16_pipe_cfg<7, 1, 1, STEER>(a, steer, s);
-  if (G % 2 == 0) return launch_attention_bf16_pipe_cfg<2, 4, 1, STEER>(a, steer, s);
-  return launch_attention_bf16_pipe_cfg<1, 8, 1, STEER>(a, steer, s);
+inline hipError_t launch_attention_bf16_pipe(const AttnArgs& a, const SteerArgs* steer, hipStream_t s) {
+  if (!steer) return launch_attention_bf16_pipe_plain(a, s);
+  const int R = steer->M * steer->r;
+  if (R <= 32) return launch_attention_bf16_pipe_r32(a, steer, s);
+  if (R <= 64) return launch_attention_bf16_pipe_r64(a, steer, s);
+  return launch_attention_bf16_pipe_r128(a, steer, s);
 }
 
 // RPW = 1: eight waves of 32 rows; RPW = 2: four waves of 64 rows
@@ -112,7 +90,7 @@ hipError_t launch_attention_bf16_variant(const AttnArgs& a, const SteerArgs* ste
   switch (variant) {
     case 0:
       if (D == 128) {
-        hipError_t e = launch_attention_bf16_pipe_group<STEER, 1>(a, steer, s);
+        hipError_t e = launch_attention_bf16_pipe(a, steer, s);
         if (e == hipErrorNotSupported) e = launch_attention_bf16_dma_group<STEER, 1>(a, steer, s);
         if (e != hipErrorNotSupported) return e;     // too much LDS for this (S, rank): use the register-staged kernel
       }
@@ -121,9 +99,6 @@ hipError_t launch_attention_bf16_variant(const AttnArgs& a, const SteerArgs* ste
     case 1: return launch_attention_bf16_group<D, STEER, 32, 0>(a, steer, s);
     case 2: return launch_attention_bf16_group<D, STEER, 32, 1>(a, steer, s);
     case 3: return D == 128 ? launch_attention_bf16_dma_group<STEER, 1>(a, steer, s) : hipErrorNotSupported;
-    case 8: return D == 128 ? launch_attention_bf16_pipe_cfg<4, 2, 1, STEER, 0>(a, steer, s) : hipErrorNotSupported;
-    case 9: return D == 128 ? launch_attention_bf16_pipe_group<STEER, 2>(a, steer, s) : hipErrorNotSupported;
-    case 10: return D == 128 ? launch_attention_bf16_pipe_cfg<4, 1, 2, STEER, 0>(a, steer, s) : hipErrorNotSupported;
     case 4: return launch_attention_bf16_cfg<D, 4, 2, STEER, 32, 0, 1>(a, steer, s);   // timing experiments (wrong results)
     case 5: return launch_attention_bf16_cfg<D, 4, 2, STEER, 32, 0, 2>(a, steer, s);
     case 6: return launch_attention_bf16_cfg<D, 4, 2, STEER, 32, 0, 3>(a, steer, s);

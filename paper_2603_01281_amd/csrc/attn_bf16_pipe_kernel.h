@@ -21,8 +21,19 @@
 
 namespace seka {
 
-inline size_t attention_bf16_pipe_smem_bytes(int S, bool steer, int Rpad) {
-  return attention_bf16_dma_smem_bytes(S, steer, Rpad);
+// LDS beyond the two tile rings (steered kernels): the concatenated basis U_cat, the per-column coefficients and
+// one 64-bit highlight word per tile.  For a rank of at most 64 (nkr <= 2) U_cat is stored twice, once per
+// product of the edit, each copy in the order the MFMA operands are read (one conflict-free 16-byte read per
+// lane and operand); for larger ranks one row-major copy serves both products (transposing reads for the first).
+inline size_t attention_bf16_pipe_smem_bytes(int S, bool steer, int nkr) {
+  size_t n = (size_t)2 * DMA_STAGES * DMA_TILE_BYTES;
+  if (steer) {
+    const int Rpad = 32 * nkr;
+    n += nkr <= 2 ? (size_t)2 * DMA_D * Rpad * 2 : (size_t)DMA_D * (Rpad + 8) * 2;
+    n += (size_t)Rpad * 4;
+    n += (size_t)((S + DMA_BK - 1) / DMA_BK) * 8;
+  }
+  return n;
 }
 
 typedef __attribute__((address_space(3))) const bf16x8* pipe_lds_bf16x8_ptr;
@@ -41,8 +52,9 @@ __device__ __forceinline__ void pipe_load_16B(const void* base, uint32_t lane_of
 
 // HPW heads x RBW row groups = waves per workgroup; every wave owns RPW blocks of 32 consecutive query rows.
 // RPW = 2 (four waves, one per SIMD, 512-register budget) reads every K / V fragment once for two products.
-template <int HPW, int RBW, int RPW, bool STEER, int SCHED = 1>
-__global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(AttnArgs a, SteerArgs st, int Rpad) {
+// NKR: rank of the concatenated basis in blocks of 32 columns (compile-time so that the edit is straight-line code).
+template <int HPW, int RBW, int RPW, bool STEER, int NKR, int SCHED = 1>
+__global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(AttnArgs a, SteerArgs st) {
   constexpr int D = DMA_D;
   constexpr int NW = HPW * RBW;
   constexpr int NT = 64 * NW;
@@ -58,9 +70,13 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   unsigned char* Kst = smem;                                     // [3][16 KB] swizzled K tiles
   unsigned char* Vst = smem + DMA_STAGES * TB;                   // [3][16 KB] swizzled V tiles
-  uint16_t* UN = reinterpret_cast<uint16_t*>(smem + 2 * DMA_STAGES * TB);   // [D][Rpad+8] (STEER)
-  const int ULD = Rpad + 8;
-  float* cvec = reinterpret_cast<float*>(UN + (size_t)D * ULD);                          // [Rpad]
+  constexpr int Rpad = 32 * NKR;
+  constexpr bool FRAG = NKR <= 2;          // operand-ordered copies of U_cat (see attention_bf16_pipe_smem_bytes)
+  constexpr int ULD = Rpad + 8;            // row-major copy: row stride in elements
+  uint16_t* UN = reinterpret_cast<uint16_t*>(smem + 2 * DMA_STAGES * TB);   // FRAG: U1 then U2; else [D][ULD]
+  uint16_t* U1 = UN;                       // operand (rb, s) of U_cat^T K^T: [2 NKR][4][64 lanes][8]
+  uint16_t* U2 = UN + D * Rpad;            // operand (s, half, kr) of U_cat Z: [4][2][NKR][64 lanes][8]
+  float* cvec = reinterpret_cast<float*>(UN + (FRAG ? (size_t)2 * D * Rpad : (size_t)D * ULD));   // [Rpad]
   unsigned long long* hlbits = reinterpret_cast<unsigned long long*>(cvec + Rpad);       // [tiles] (STEER)
 
   const uint16_t* __restrict__ Qg = static_cast<const uint16_t*>(a.Q);
@@ -148,11 +164,12 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     }
   }
 
-  // ---- steering set-up: U_cat (row d, r contiguous), per-column coefficients, highlight bitmap ----
+  // ---- steering set-up: U_cat, per-column coefficients, highlight bitmap ----
   if (STEER && steer_on) {
     const int R = st.M * st.r;
     if (R != Rpad) {
-      for (int i = tid; i < D * ULD; i += NT) UN[i] = 0;
+      const int n16 = (FRAG ? 2 * D * Rpad : D * ULD) / 8;
+      for (int i = tid; i < n16; i += NT) reinterpret_cast<uint4*>(UN)[i] = make_uint4(0, 0, 0, 0);
       __syncthreads();
     }
     const uint16_t* Uh = static_cast<const uint16_t*>(st.U) + (size_t)h * st.M * D * st.r;
@@ -161,23 +178,72 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     for (int idx = tid; idx < total; idx += NT) {
       const int m = idx / (D * r8), rm = idx % (D * r8);
       const int d = rm / r8, v = rm % r8;
-      *reinterpret_cast<uint4*>(UN + (size_t)d * ULD + m * st.r + 8 * v) =
-          *reinterpret_cast<const uint4*>(Uh + ((size_t)m * D + d) * st.r + 8 * v);
+      const uint4 val = *reinterpret_cast<const uint4*>(Uh + ((size_t)m * D + d) * st.r + 8 * v);
+      const int r0 = m * st.r + 8 * v;              // concatenated column of the first of these 8 elements
+      if (FRAG) {
+        const uint16_t* e16 = reinterpret_cast<const uint16_t*>(&val);
+        // first product: operand (rb, s), lane (g, j) holds U_cat[d = 32 s + 8 g + e][r = 16 rb + j], e = 0..7
+        const int s1 = d >> 5, g1 = (d >> 3) & 3, e1 = d & 7;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int r = r0 + i;
+          U1[((((r >> 4) * 4 + s1) * 64) + g1 * 16 + (r & 15)) * 8 + e1] = e16[i];
+        }
+        // second product: operand (s, half, kr), lane (g, j) holds U_cat[d = 32 s + 8 (j / 4) + 4 half + j % 4]
+        // [r = 32 kr + 16 (e / 4) + 4 g + e % 4], e = 0..7: four consecutive columns are four consecutive slots
+        const int dl = d & 31, j2 = 4 * (dl >> 3) + (dl & 3), half2 = (dl >> 2) & 1;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+          const int r = r0 + 4 * q, rl = r & 31;
+          uint16_t* dst = U2 + (((((s1 * 2 + half2) * NKR + (r >> 5)) * 64) + ((rl & 15) >> 2) * 16 + j2) * 8 + 4 * (rl >> 4));
+          *reinterpret_cast<uint2*>(dst) = q == 0 ? make_uint2(val.x, val.y) : make_uint2(val.z, val.w);
+        }
+      } else {
+        *reinterpret_cast<uint4*>(UN + (size_t)d * ULD + r0) = val;
+      }
     }
     for (int r = tid; r < Rpad; r += NT) {
       float c = 0.f;
       if (r < R) c = gain * (st.w ? st.w[((size_t)b * a.Hkv + h) * st.M + r / st.r] : 1.f);
       cvec[r] = c;
     }
-    for (int t = wave; t < ntiles; t += NW) {
-      const int key = t * BK + lane;
-      const int mk = key < S ? st.mask[(size_t)b * S + key] : 0;
-      const unsigned long long bits = __ballot(mk != 0);
-      if (lane == 0) hlbits[t] = bits;
+    // one 64-bit word per tile, one thread per tile: bit k = key 64 t + k is highlighted
+    const uint8_t* mrow = st.mask + (size_t)b * S;
+    const bool wide = (reinterpret_cast<uintptr_t>(mrow) & 15) == 0;
+    for (int t = tid; t < ntiles; t += NT) {
+      unsigned long long bits = 0ull;
+      if (wide && t * BK + BK <= S) {
+        const uint4* mp = reinterpret_cast<const uint4*>(mrow + (size_t)t * BK);
+#pragma unroll
+        for (int q = 0; q < BK / 16; ++q) {
+          const uint4 mv = mp[q];
+          const uint32_t x4[4] = {mv.x, mv.y, mv.z, mv.w};
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            // non-zero test of the four bytes of x, gathered into four adjacent bits
+            const uint32_t x = x4[w];
+            const uint32_t y = ((x | ((x & 0x7f7f7f7fu) + 0x7f7f7f7fu)) & 0x80808080u) >> 7;
+            const uint32_t nib = ((y * 0x00204081u) >> 21) & 0xfu;
+            bits |= (unsigned long long)nib << (16 * q + 4 * w);
+          }
+        }
+      } else {
+        for (int k = 0; k < BK; ++k)
+          if (t * BK + k < S && mrow[(size_t)t * BK + k] != 0) bits |= 1ull << k;
+      }
+      hlbits[t] = bits;
     }
   }
+  // Which of the 64 tiles [tile0, tile0 + 64) hold a highlighted key: kept in scalar registers so that the common
+  // case (nothing to edit) costs no LDS access.  Valid once the bitmap is complete (after the first barrier).
+  auto any_word = [&](int tile0) __attribute__((always_inline)) -> unsigned long long {
+    const int idx = tile0 + lane;
+    const unsigned long long v = (steer_on && idx < ntiles) ? hlbits[idx] : 0ull;
+    return __ballot(v != 0ull);
+  };
 
-  // Edit the highlighted 16-key blocks of the (swizzled) K tile at Kb; one wave per block.
+  // Edit the highlighted 16-key blocks of the (swizzled) K tile at Kb: wave w < 4 owns block w.  What bounds the
+  // edit is LDS traffic for U_cat (every block reads all of it, twice), so the blocks are not split further.
   auto edit_tile = [&](unsigned char* Kb, unsigned long long bits) __attribute__((always_inline)) {
     // The lane index is re-derived behind an opaque copy so that none of the per-lane operand addresses below
     // is hoisted out of the tile loop: they would occupy registers the attention pipeline needs.
@@ -185,68 +251,73 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     asm volatile("" : "+v"(ln));
     const int j = ln & 15, g = ln >> 4;
     constexpr int KS2 = D / 32;
-    constexpr int MAXKR = SEKA_MAX_RANK / 32;
-    const int nkr = Rpad / 32;
-    for (int kblk = wave; kblk < BK / 16; kblk += NW) {
-      const unsigned bits16 = (unsigned)((bits >> (16 * kblk)) & 0xffffull);
-      if (bits16 == 0) continue;
-      unsigned char* krow = Kb + (16 * kblk + j) * 256;    // row & 15 == j
-      bf16x8 kreg[KS2];   // K^T as B operand: lane (col = key j, k = d = 32 s + 8 g + e) = logical chunk 4 s + g
-  #pragma unroll
-      for (int s = 0; s < KS2; ++s) kreg[s] = *reinterpret_cast<const bf16x8*>(krow + 16 * ((4 * s + g) ^ j));
-      const float mbit = ((bits16 >> j) & 1u) ? 1.f : 0.f;
-      const uint16_t* ut = UN + (size_t)(8 * g + (j >> 2)) * ULD + 4 * (j & 3);
-      bf16x8 zb[MAXKR];
-  #pragma unroll
-      for (int kr = 0; kr < MAXKR; ++kr) {
-        if (kr < nkr) {
-          float zc[8];
-  #pragma unroll
-          for (int half = 0; half < 2; ++half) {
-            const int rb = 2 * kr + half;
-            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  #pragma unroll
-            for (int s = 0; s < KS2; ++s) {
-              const uint16_t* p = ut + (size_t)(32 * s) * ULD + 16 * rb;
-              const bf16x8 ua = dma_read_tr_pair(reinterpret_cast<const unsigned char*>(p),
-                                                 reinterpret_cast<const unsigned char*>(p + 4 * ULD));
-              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua, kreg[s], acc, 0, 0, 0);
-            }
-            const f32x4 c4 = *reinterpret_cast<const f32x4*>(cvec + 16 * rb + 4 * g);
-  #pragma unroll
-            for (int i = 0; i < 4; ++i) zc[4 * half + i] = acc[i] * c4[i] * mbit;
+    const int kblk = wave;
+    const unsigned bits16 = (unsigned)((bits >> (16 * (kblk & 3))) & 0xffffull);
+    if (kblk >= BK / 16 || bits16 == 0) return;           // wave-uniform
+    unsigned char* krow = Kb + (16 * kblk + j) * 256;     // row & 15 == j
+    bf16x8 kreg[KS2];   // K^T as B operand: lane (col = key j, k = d = 32 s + 8 g + e) = logical chunk 4 s + g
+#pragma unroll
+    for (int s = 0; s < KS2; ++s) kreg[s] = *reinterpret_cast<const bf16x8*>(krow + 16 * ((4 * s + g) ^ j));
+    const float mbit = ((bits16 >> j) & 1u) ? 1.f : 0.f;
+    // z^T = U_cat^T K^T (rows r, columns keys), scaled by the per-column coefficient and the key's mask bit
+    bf16x8 zb[NKR];
+    const uint16_t* ut = UN + (size_t)(8 * g + (j >> 2)) * ULD + 4 * (j & 3);      // row-major copy (not FRAG)
+#pragma unroll
+    for (int kr = 0; kr < NKR; ++kr) {
+      float zc[8];
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        const int rb = 2 * kr + half;
+        f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};   // two chains: even and odd slices of d
+#pragma unroll
+        for (int s = 0; s < KS2; ++s) {
+          bf16x8 ua;
+          if (FRAG) {
+            ua = *reinterpret_cast<const bf16x8*>(U1 + ((rb * 4 + s) * 64 + ln) * 8);
+          } else {
+            const uint16_t* p = ut + (size_t)(32 * s) * ULD + 16 * rb;
+            ua = dma_read_tr_pair(reinterpret_cast<const unsigned char*>(p),
+                                  reinterpret_cast<const unsigned char*>(p + 4 * ULD));
           }
-          bf16x8 z;   // next B operand: slot e <-> r = 32 kr + 16 (e / 4) + 4 g + e % 4
-  #pragma unroll
-          for (int e = 0; e < 8; ++e) z[e] = (__bf16)zc[e];
-          zb[kr] = z;
+          acc[s & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua, kreg[s], acc[s & 1], 0, 0, 0);
         }
+        const f32x4 c4 = *reinterpret_cast<const f32x4*>(cvec + 16 * rb + 4 * g);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) zc[4 * half + i] = (acc[0][i] + acc[1][i]) * (c4[i] * mbit);
       }
-  #pragma unroll
-      for (int s = 0; s < KS2; ++s) {
-        float outv[8];
-  #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-          const int d_row = 32 * s + 8 * (j >> 2) + 4 * half + (j & 3);
-          f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  #pragma unroll
-          for (int kr = 0; kr < MAXKR; ++kr) {
-            if (kr < nkr) {
-              const uint16_t* p = UN + (size_t)d_row * ULD + 32 * kr + 4 * g;
-              const bf16x4 u0 = *reinterpret_cast<const bf16x4*>(p);
-              const bf16x4 u1 = *reinterpret_cast<const bf16x4*>(p + 16);
-              const bf16x8 ua = __builtin_shufflevector(u0, u1, 0, 1, 2, 3, 4, 5, 6, 7);
-              acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua, zb[kr], acc, 0, 0, 0);
-            }
+      bf16x8 z;   // next B operand: slot e <-> r = 32 kr + 16 (e / 4) + 4 g + e % 4
+#pragma unroll
+      for (int e = 0; e < 8; ++e) z[e] = (__bf16)zc[e];
+      zb[kr] = z;
+    }
+    // k' = k + U_cat z: output rows d permuted so that each result lands in the lane holding that element of k
+#pragma unroll
+    for (int s = 0; s < KS2; ++s) {
+      float outv[8];
+#pragma unroll
+      for (int half = 0; half < 2; ++half) {
+        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kr = 0; kr < NKR; ++kr) {
+          bf16x8 ua;
+          if (FRAG) {
+            ua = *reinterpret_cast<const bf16x8*>(U2 + (((s * 2 + half) * NKR + kr) * 64 + ln) * 8);
+          } else {
+            const int d_row = 32 * s + 8 * (j >> 2) + 4 * half + (j & 3);
+            const uint16_t* p = UN + (size_t)d_row * ULD + 32 * kr + 4 * g;
+            const bf16x4 u0 = *reinterpret_cast<const bf16x4*>(p);
+            const bf16x4 u1 = *reinterpret_cast<const bf16x4*>(p + 16);
+            ua = __builtin_shufflevector(u0, u1, 0, 1, 2, 3, 4, 5, 6, 7);
           }
-  #pragma unroll
-          for (int i = 0; i < 4; ++i) outv[4 * half + i] = (float)kreg[s][4 * half + i] + acc[i];
+          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua, zb[kr], acc, 0, 0, 0);
         }
-        bf16x8 o;
-  #pragma unroll
-        for (int e = 0; e < 8; ++e) o[e] = (__bf16)outv[e];
-        *reinterpret_cast<bf16x8*>(krow + 16 * ((4 * s + g) ^ j)) = o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) outv[4 * half + i] = (float)kreg[s][4 * half + i] + acc[i];
       }
+      bf16x8 o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = (__bf16)outv[e];
+      *reinterpret_cast<bf16x8*>(krow + 16 * ((4 * s + g) ^ j)) = o;
     }
   };
 
@@ -380,12 +451,12 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[rp][ks]));   // pin the compiler's own wait for Q here, not in the loop
   dma_barrier();
-  if (STEER && steer_on) {
-    const unsigned long long hl0 = hlbits[0];
-    const unsigned long long hl1 = ntiles > 1 ? hlbits[1] : 0ull;
-    if ((hl0 | hl1) != 0ull) {
-      if (hl0 != 0ull) edit_tile(Kst, hl0);
-      if (hl1 != 0ull) edit_tile(Kst + TB, hl1);
+  unsigned long long anyw = 0ull;      // bit i: tile 64 (t / 64) + i holds a highlighted key (0 when not steering)
+  if (STEER) {
+    anyw = any_word(0);
+    if (anyw & 3ull) {
+      if (anyw & 1ull) edit_tile(Kst, hlbits[0]);
+      if (anyw & 2ull) edit_tile(Kst + TB, hlbits[1]);
       dma_barrier();
     }
   }
@@ -409,11 +480,16 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     if (t + 2 < ntiles) dma_wait_vmcnt<SPW>();
     else dma_wait_vmcnt<0>();
     dma_barrier();
-    if (STEER && steer_on && t + 2 < ntiles) {
-      const unsigned long long hl = hlbits[t + 2];
-      if (hl != 0ull) {
-        edit_tile(Kst + ((t + 2) % 3) * TB, hl);
-        dma_barrier();
+    if (STEER) {
+      // one scalar branch in the common case; tiles past the end and unsteered heads have no bit set
+      const int tn = t + 2;
+      const unsigned sh = tn & 63;
+      if (__builtin_expect((((anyw >> sh) & 1ull) != 0ull) | (sh == 0u), 0)) {
+        if (sh == 0u) anyw = any_word(tn);
+        if ((anyw >> sh) & 1ull) {
+          edit_tile(Kst + (tn % 3) * TB, hlbits[tn]);
+          dma_barrier();
+        }
       }
     }
   };

@@ -1,0 +1,7 @@
+// Software-pipelined bf16 attention, head dimension 128: steered kernels for a concatenated rank of at most 32.
+#include "attn_bf16_pipe_launch.h"
+namespace seka {
+hipError_t launch_attention_bf16_pipe_r32(const AttnArgs& a, const SteerArgs* steer, hipStream_t s) {
+  return launch_attention_bf16_pipe_group<true, 1>(a, steer, s);
+}
+}  // namespace seka

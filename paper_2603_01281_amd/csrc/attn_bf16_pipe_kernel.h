@@ -130,9 +130,10 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   const size_t head_off = ((size_t)b * S * a.Hkv + h) * D * 2;          // bytes to this (batch, KV head), token 0
   const unsigned char* Kbytes = reinterpret_cast<const unsigned char*>(Kg) + head_off;
   const unsigned char* Vbytes = reinterpret_cast<const unsigned char*>(Vg) + head_off;
-  auto issue_rows = [&](const unsigned char* tensor, int t, uint32_t lds_stage_base, const uint32_t (&off)[SPW]) {
+  auto issue_rows = [&](auto full_c, const unsigned char* tensor, int t, uint32_t lds_stage_base,
+                        const uint32_t (&off)[SPW]) __attribute__((always_inline)) {
     const unsigned char* tile = tensor + (size_t)t * BK * rowbytes;
-    if (t * BK + BK <= S) {
+    if (decltype(full_c)::value || t * BK + BK <= S) {
 #pragma unroll
       for (int n = 0; n < SPW; ++n) pipe_load_16B(tile, off[n], lds_stage_base + slot_lds[n]);
     } else {
@@ -142,8 +143,12 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
         pipe_load_16B(tile, off[n] - (uint32_t)max(0, slot_row[n] - last_row) * rowbytes, lds_stage_base + slot_lds[n]);
     }
   };
-  auto issue_k = [&](int t) __attribute__((always_inline)) { issue_rows(Kbytes, t, kst_base + (t % 3) * TB, koff); };
-  auto issue_v = [&](int t) __attribute__((always_inline)) { issue_rows(Vbytes, t, vst_base + (t % 3) * TB, voff); };
+  auto issue_k = [&](int t) __attribute__((always_inline)) {
+    issue_rows(std::false_type{}, Kbytes, t, kst_base + (t % 3) * TB, koff);
+  };
+  auto issue_v = [&](int t) __attribute__((always_inline)) {
+    issue_rows(std::false_type{}, Vbytes, t, vst_base + (t % 3) * TB, voff);
+  };
 
   issue_k(0);
   issue_v(0);
@@ -470,14 +475,20 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 
   // Top of iteration t: request K(t+2) and V(t+2) (in this order).  Bottom: K(t+2) and V(t+1) must have landed
   // before the next iteration (V(t+2) stays in flight); then edit K(t+2) if it holds highlighted keys.
-  auto top = [&](int t) __attribute__((always_inline)) {
-    if (t + 2 < ntiles) {
+  // The hot loop only runs where tile t + 2 exists and is complete (`sure`): no tests there.
+  auto top = [&](auto sure_c, auto stage_c, int t) __attribute__((always_inline)) {
+    constexpr bool SURE = decltype(sure_c)::value;
+    if (SURE) {
+      constexpr int ST2 = (decltype(stage_c)::value + 2) % 3;
+      issue_rows(std::true_type{}, Kbytes, t + 2, kst_base + ST2 * TB, koff);
+      issue_rows(std::true_type{}, Vbytes, t + 2, vst_base + ST2 * TB, voff);
+    } else if (t + 2 < ntiles) {
       issue_k(t + 2);
       issue_v(t + 2);
     }
   };
-  auto bottom = [&](int t) __attribute__((always_inline)) {
-    if (t + 2 < ntiles) dma_wait_vmcnt<SPW>();
+  auto bottom = [&](auto sure_c, int t) __attribute__((always_inline)) {
+    if (decltype(sure_c)::value || t + 2 < ntiles) dma_wait_vmcnt<SPW>();
     else dma_wait_vmcnt<0>();
     dma_barrier();
     if (STEER) {
@@ -549,45 +560,50 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   auto hot = [&](auto st_c, int t) __attribute__((always_inline)) {
     constexpr int ST = decltype(st_c)::value;
     using std::integral_constant;
-    top(t);
+    top(std::true_type{}, st_c, t);
     step(integral_constant<int, ST * TB + 32 * 256>{}, integral_constant<int, ST * TB>{}, sc0, sc1);
     step(integral_constant<int, ((ST + 1) % 3) * TB>{}, integral_constant<int, ST * TB + 32 * 256>{}, sc1, sc0);
-    bottom(t);
+    bottom(std::true_type{}, t);
   };
 
+  // Hot iterations: tile t is seen in full by every row of this wave, and tile t + 2 exists and is complete.
+  const int t_hot = min(tw_last, min(ntiles, S / BK) - 2);
   int t = 0;
-  if (tw_last > 0) {
+  if (t_hot > 0) {
     using std::integral_constant;
     for (;;) {
-      hot(integral_constant<int, 0>{}, t); if (++t == tw_last) break;
-      hot(integral_constant<int, 1>{}, t); if (++t == tw_last) break;
-      hot(integral_constant<int, 2>{}, t); if (++t == tw_last) break;
+      hot(integral_constant<int, 0>{}, t); if (++t == t_hot) break;
+      hot(integral_constant<int, 1>{}, t); if (++t == t_hot) break;
+      hot(integral_constant<int, 2>{}, t); if (++t == t_hot) break;
     }
   }
-  // ---- the wave's last tile (causal mask, nothing further to score), then idle turns while other waves finish ----
+  // ---- the remaining tiles, unpipelined: up to two before the wave's last tile, the last tile (causal mask),
+  // then idle turns while other waves of the workgroup finish ----
 #pragma nounroll
-  for (t = max(tw_last, 0); t < ntiles; ++t) {
-    top(t);
-    if (t == tw_last) {
+  for (; t < ntiles; ++t) {
+    top(std::false_type{}, IC0{}, t);
+    if (t <= tw_last) {
       const int off = (t % 3) * TB;
+      const bool diag = t == tw_last;
       bf16x8 pb[RPW][2];
       qk_part(IC0{}, ICK{}, off + 32 * 256, sc1);
 #pragma unroll
       for (int rp = 0; rp < RPW; ++rp) {
-        causal_mask(t * BK, rp, sc0[rp]);
+        if (diag) causal_mask(t * BK, rp, sc0[rp]);
         raise_reference(rp, block_max(sc0[rp]));
         block_exp(rp, sc0[rp], pb[rp]);
       }
       pv_half(off, pb);
 #pragma unroll
       for (int rp = 0; rp < RPW; ++rp) {
-        causal_mask(t * BK + 32, rp, sc1[rp]);
+        if (diag) causal_mask(t * BK + 32, rp, sc1[rp]);
         raise_reference(rp, block_max(sc1[rp]));
         block_exp(rp, sc1[rp], pb[rp]);
       }
       pv_half(off + 32 * 256, pb);
+      if (!diag) qk_part(IC0{}, ICK{}, ((t + 1) % 3) * TB, sc0);     // K(t+1) landed (and was edited) an iteration ago
     }
-    bottom(t);
+    bottom(std::false_type{}, t);
   }
 
   // ---- epilogue ----

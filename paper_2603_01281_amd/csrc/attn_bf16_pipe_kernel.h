@@ -67,6 +67,11 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   constexpr int SPW = (SLOTS + NW - 1) / NW;             // load instructions per wave per tensor per tile
   constexpr int TB = DMA_TILE_BYTES;
 
+#ifdef SEKA_CYCLE_PROBE
+  // Diagnostic build: per-wave shader-clock counters, written over the LSE rows of the wave's first queries.
+  const unsigned long long prb_entry = __builtin_amdgcn_s_memtime();
+  unsigned long long prb_edit = 0ull, prb_n = 0ull, prb_wait = 0ull, prb_bar = 0ull;
+#endif
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   unsigned char* Kst = smem;                                     // [3][16 KB] swizzled K tiles
   unsigned char* Vst = smem + DMA_STAGES * TB;                   // [3][16 KB] swizzled V tiles
@@ -456,6 +461,10 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[rp][ks]));   // pin the compiler's own wait for Q here, not in the loop
   dma_barrier();
+#ifdef SEKA_CYCLE_PROBE
+  const unsigned long long prb_start = __builtin_amdgcn_s_memtime();
+  const unsigned long long prb_rstart = __builtin_amdgcn_s_memrealtime();
+#endif
   unsigned long long anyw = 0ull;      // bit i: tile 64 (t / 64) + i holds a highlighted key (0 when not steering)
   if (STEER) {
     anyw = any_word(0);
@@ -488,9 +497,20 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     }
   };
   auto bottom = [&](auto sure_c, int t) __attribute__((always_inline)) {
+#ifdef SEKA_CYCLE_PROBE
+    const unsigned long long w0 = __builtin_amdgcn_s_memtime();
+#endif
     if (decltype(sure_c)::value || t + 2 < ntiles) dma_wait_vmcnt<SPW>();
     else dma_wait_vmcnt<0>();
+#ifdef SEKA_CYCLE_PROBE
+    const unsigned long long w1 = __builtin_amdgcn_s_memtime();
     dma_barrier();
+    const unsigned long long w2 = __builtin_amdgcn_s_memtime();
+    prb_wait += w1 - w0;
+    prb_bar += w2 - w1;
+#else
+    dma_barrier();
+#endif
     if (STEER) {
       // one scalar branch in the common case; tiles past the end and unsteered heads have no bit set
       const int tn = t + 2;
@@ -498,8 +518,15 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
       if (__builtin_expect((((anyw >> sh) & 1ull) != 0ull) | (sh == 0u), 0)) {
         if (sh == 0u) anyw = any_word(tn);
         if ((anyw >> sh) & 1ull) {
+#ifdef SEKA_CYCLE_PROBE
+          const unsigned long long c0 = __builtin_amdgcn_s_memtime();
+#endif
           edit_tile(Kst + (tn % 3) * TB, hlbits[tn]);
           dma_barrier();
+#ifdef SEKA_CYCLE_PROBE
+          prb_edit += __builtin_amdgcn_s_memtime() - c0;
+          prb_n += 1;
+#endif
         }
       }
     }
@@ -624,6 +651,19 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
           *reinterpret_cast<uint2*>(op + 32 * db + 8 * q4) = __builtin_bit_cast(uint2, o4);
         }
       }
+#ifdef SEKA_CYCLE_PROBE
+      if (a.lse && lane == 0 && rp == 0) {
+        float* dp = a.lse + ((size_t)b * a.Hq + hq) * S + qi;
+        dp[0] = (float)(prb_start - prb_entry);                          // set-up until the first tiles are usable
+        dp[1] = (float)(__builtin_amdgcn_s_memtime() - prb_start);       // loop and epilogue
+        dp[2] = (float)(__builtin_amdgcn_s_memrealtime() - prb_rstart);  // the same span in 100 MHz ticks
+        dp[3] = (float)prb_wait;                                         // waiting for tile loads
+        dp[4] = (float)prb_bar;                                          // waiting at the per-tile barrier
+        dp[5] = (float)prb_edit;                                         // key edits incl. their barrier
+        dp[6] = (float)prb_n;
+      }
+      if (false)
+#endif
       // m_run is the reference exponent in units of s * scale * log2(e); l_tot is relative to it
       if (a.lse && hf == 0) a.lse[((size_t)b * a.Hq + hq) * S + qi] = m_run[rp] * 0.6931471805599453f + logf(l_tot);
     }

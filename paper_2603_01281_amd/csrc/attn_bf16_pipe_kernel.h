@@ -38,6 +38,14 @@ inline size_t attention_bf16_pipe_smem_bytes(int S, bool steer, int nkr) {
 
 typedef __attribute__((address_space(3))) const bf16x8* pipe_lds_bf16x8_ptr;
 
+// The compiler does not insert, before inline assembly, the wait states an MFMA result needs before a vector
+// instruction may read it.  pipe_max3 is only used on scores whose MFMAs are provably far behind: in the
+// pipelined loop they belong to the previous step (a scheduling barrier and eight MFMAs apart); elsewhere
+// pipe_mfma_result_guard() is placed between the product and the maximum.
+__device__ __forceinline__ void pipe_mfma_result_guard(f32x16& acc) {
+  asm volatile("s_nop 15\n\ts_nop 15" : "+v"(acc));
+}
+
 __device__ __forceinline__ float pipe_max3(float a, float b, float c) {
   float r;
   asm("v_max3_f32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
@@ -480,7 +488,11 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   for (int rp = 0; rp < RPW; ++rp)
 #pragma unroll
     for (int r = 0; r < 16; ++r) { sc0[rp][r] = 0.f; sc1[rp][r] = 0.f; }
-  if (0 <= tw_last) qk_part(IC0{}, ICK{}, 0, sc0);
+  if (0 <= tw_last) {
+    qk_part(IC0{}, ICK{}, 0, sc0);
+#pragma unroll
+    for (int rp = 0; rp < RPW; ++rp) pipe_mfma_result_guard(sc0[rp]);
+  }
 
   // Top of iteration t: request K(t+2) and V(t+2) (in this order).  Bottom: K(t+2) and V(t+1) must have landed
   // before the next iteration (V(t+2) stays in flight); then edit K(t+2) if it holds highlighted keys.
@@ -616,6 +628,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
       qk_part(IC0{}, ICK{}, off + 32 * 256, sc1);
 #pragma unroll
       for (int rp = 0; rp < RPW; ++rp) {
+        pipe_mfma_result_guard(sc0[rp]);
         if (diag) causal_mask(t * BK, rp, sc0[rp]);
         raise_reference(rp, block_max(sc0[rp]));
         block_exp(rp, sc0[rp], pb[rp]);
@@ -623,6 +636,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
       pv_half(off, pb);
 #pragma unroll
       for (int rp = 0; rp < RPW; ++rp) {
+        pipe_mfma_result_guard(sc1[rp]);
         if (diag) causal_mask(t * BK + 32, rp, sc1[rp]);
         raise_reference(rp, block_max(sc1[rp]));
         block_exp(rp, sc1[rp], pb[rp]);

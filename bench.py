@@ -23,6 +23,12 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
 
+# HBM bytes of one fused steered launch at this workload, from hardware counters (rocprofv3 --pmc FETCH_SIZE and
+# --pmc WRITE_SIZE runs of this script, each scaled by what the same counter reads for a 256 MiB device copy:
+# x2.0 for FETCH_SIZE, x1.0 for WRITE_SIZE; summary in profiles/attention_bf16_cfg3_hbm_traffic.md).
+# Algorithmic bytes are Q + K + V + O = 671 MB; the rest is K/V re-fetched by workgroups on different XCDs.
+MEASURED_TRAFFIC_BYTES = {"fetch": 750756.0 * 1024 * 2.0, "write": 262145.0 * 1024 * 1.0}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -197,9 +203,12 @@ def main():
         "tokens_per_s": round(B * S * L / (ms_per_step * 1e-3)),
         "steered_layer_ms": round(st_ms, 4), "plain_layer_ms": round(pl_ms, 4),
         "steering_overhead_pct": round(100 * (st_ms / pl_ms - 1), 2) if pl and steered_ix else None,
-        "roofline": {"bound": "mfma", "kernel": "attention_bf16_kernel<D=128, 4 heads x 64 rows, STEER> (seka_attention_prefill)",
+        "roofline": {"bound": "mfma", "kernel": "attention_bf16_pipe_kernel<4 heads x 64 rows, steered, rank <= 32> (seka_attention_prefill)",
                      "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                     "traffic": round(sum(MEASURED_TRAFFIC_BYTES.values())) if L == 32 and B == 4 and S == 8192 else None,
+                     "traffic_unit": "bytes per launch (offline counter runs, see profiles/)",
+                     "algorithmic_bytes": 2 * (2 * B * S * Hq * D + 2 * B * S * Hkv * D),
                      "flops_per_launch": fl_layer, "launch_ms": round(st_ms, 4)},
     }
     if args.copy_calib:

@@ -1,7 +1,7 @@
 // Launch-side dispatch of the bf16 attention kernel for one head dimension (instantiated per D in its own
 // translation unit so the variants compile in parallel).
 #pragma once
-#include "attn_bf16_dma_kernel.h"
+#include <cstring>
 #include "attn_bf16_kernel.h"
 
 namespace seka {
@@ -27,26 +27,6 @@ hipError_t launch_attention_bf16_cfg(const AttnArgs& a, const SteerArgs* steer, 
   return hipGetLastError();
 }
 
-// direct-to-LDS kernel (head dimension 128 only)
-template <int HPW, int RBW, int RPW, bool STEER>
-hipError_t launch_attention_bf16_dma_cfg(const AttnArgs& a, const SteerArgs* steer, hipStream_t s) {
-  constexpr int BQ = 32 * RPW * RBW;
-  const int Rpad = STEER ? (steer->M * steer->r + 31) / 32 * 32 : 0;
-  const size_t smem = attention_bf16_dma_smem_bytes(a.S, STEER, Rpad);
-  if (smem > 160 * 1024) return hipErrorNotSupported;
-  auto kernel = attention_bf16_dma_kernel<HPW, RBW, RPW, STEER>;
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-  if (e != hipSuccess) return e;
-  const int nQB = (a.S + BQ - 1) / BQ;
-  const long long blocks = (long long)nQB * (a.Hq / HPW) * a.B;
-  if (blocks > 0x7fffffffLL) return hipErrorNotSupported;
-  SteerArgs sa;
-  if (STEER) sa = *steer; else memset(&sa, 0, sizeof(sa));
-  hipLaunchKernelGGL(kernel, dim3((unsigned)blocks), dim3(64 * HPW * RBW), smem, s, a, sa, Rpad);
-  return hipGetLastError();
-}
-
 // software-pipelined direct-to-LDS kernels (head dimension 128 only; defined in attn_bf16_pipe_*.hip)
 hipError_t launch_attention_bf16_pipe_plain(const AttnArgs& a, hipStream_t s);
 hipError_t launch_attention_bf16_pipe_r32(const AttnArgs& a, const SteerArgs* steer, hipStream_t s);
@@ -59,21 +39,6 @@ inline hipError_t launch_attention_bf16_pipe(const AttnArgs& a, const SteerArgs*
   if (R <= 32) return launch_attention_bf16_pipe_r32(a, steer, s);
   if (R <= 64) return launch_attention_bf16_pipe_r64(a, steer, s);
   return launch_attention_bf16_pipe_r128(a, steer, s);
-}
-
-// RPW = 1: eight waves of 32 rows; RPW = 2: four waves of 64 rows
-template <bool STEER, int RPW>
-hipError_t launch_attention_bf16_dma_group(const AttnArgs& a, const SteerArgs* steer, hipStream_t s) {
-  const int G = a.Hq / a.Hkv;
-  if (RPW == 2) {
-    if (G % 4 == 0) return launch_attention_bf16_dma_cfg<4, 1, 2, STEER>(a, steer, s);
-    if (G % 2 == 0) return launch_attention_bf16_dma_cfg<2, 2, 2, STEER>(a, steer, s);
-    return launch_attention_bf16_dma_cfg<1, 4, 2, STEER>(a, steer, s);
-  }
-  if (G % 4 == 0) return launch_attention_bf16_dma_cfg<4, 2, 1, STEER>(a, steer, s);
-  if (G % 7 == 0) return launch_attention_bf16_dma_cfg<7, 1, 1, STEER>(a, steer, s);
-  if (G % 2 == 0) return launch_attention_bf16_dma_cfg<2, 4, 1, STEER>(a, steer, s);
-  return launch_attention_bf16_dma_cfg<1, 8, 1, STEER>(a, steer, s);
 }
 
 template <int D, bool STEER, int VPAD, int MODE>
@@ -90,15 +55,13 @@ hipError_t launch_attention_bf16_variant(const AttnArgs& a, const SteerArgs* ste
   switch (variant) {
     case 0:
       if (D == 128) {
-        hipError_t e = launch_attention_bf16_pipe(a, steer, s);
-        if (e == hipErrorNotSupported) e = launch_attention_bf16_dma_group<STEER, 1>(a, steer, s);
-        if (e != hipErrorNotSupported) return e;     // too much LDS for this (S, rank): use the register-staged kernel
+        const hipError_t e = launch_attention_bf16_pipe(a, steer, s);
+        if (e != hipErrorNotSupported) return e;     // highlight bitmap too large for LDS at this S: register-staged kernel
       }
       return launch_attention_bf16_group<D, STEER, 32, 0>(a, steer, s);
 #ifdef SEKA_TUNING_VARIANTS
     case 1: return launch_attention_bf16_group<D, STEER, 32, 0>(a, steer, s);
     case 2: return launch_attention_bf16_group<D, STEER, 32, 1>(a, steer, s);
-    case 3: return D == 128 ? launch_attention_bf16_dma_group<STEER, 1>(a, steer, s) : hipErrorNotSupported;
     case 4: return launch_attention_bf16_cfg<D, 4, 2, STEER, 32, 0, 1>(a, steer, s);   // timing experiments (wrong results)
     case 5: return launch_attention_bf16_cfg<D, 4, 2, STEER, 32, 0, 2>(a, steer, s);
     case 6: return launch_attention_bf16_cfg<D, 4, 2, STEER, 32, 0, 3>(a, steer, s);

@@ -1,5 +1,14 @@
-// Software-pipelined direct-to-LDS attention kernel (head dimension 128, 32 query rows per wave; see
-// attn_bf16_dma_kernel.h for the tile transport, the swizzle and the math mapping).
+// bf16 causal GQA prefill attention for gfx950, head dimension 128, with the spectral key edit fused in
+// (paper Sec. 2: logits q_i . k'_j / sqrt(d_k), k'_j = k_j + g P k_j for highlighted j; Sec. 3.3 for the
+// blended P of AdaSEKA).  Flash-style: scores and edited keys never leave the CU.  Software-pipelined,
+// 32 query rows per wave; attn_bf16_lds_dma.h describes how the tiles travel.
+//
+// Math mapping: S^T = K Q^T on v_mfma_f32_32x32x16_bf16 with A = K rows from LDS and B = Q fragments resident
+// in registers, so each lane owns one query row and 16 of a block's 32 keys (row maximum and sum are in-lane
+// plus one exchange with lane ^ 32); O^T = V^T P^T with B = P^T taken straight from the S^T accumulators (the
+// contraction order over keys is permuted identically on the V side) and A = V^T fetched from the row-major V
+// tile with the transposing LDS read ds_read_b64_tr_b16.  A workgroup is HPW query heads of one KV group x
+// RBW blocks of 32 query rows, all sharing the K/V tiles (and the edit) of that KV head.
 //
 // What bounds this kernel on gfx950 is the SIMD's vector issue port, not the matrix pipe: a 32x32x16 bf16
 // MFMA holds the port for about 16 cycles of its 32, a plain vector instruction for 4, an exponential for
@@ -17,7 +26,7 @@
 #pragma once
 #include <type_traits>
 
-#include "attn_bf16_dma_kernel.h"
+#include "attn_bf16_lds_dma.h"
 
 namespace seka {
 

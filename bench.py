@@ -40,7 +40,7 @@ def parse():
     ap.add_argument("--copy-calib", action="store_true",
                     help="also run one device copy of a known size (256 MiB read + 256 MiB written) so that "
                          "hardware byte counters can be scaled against it")
-    ap.add_argument("--extras", action="store_true", help="also time configurations 2, 4, 5 (reported inside the same JSON line)")
+    ap.add_argument("--extras", action="store_true", help="also time single layers of configurations 2-5, with seka_route and seka_edit_keys (reported inside the same JSON line)")
     return ap.parse_args()
 
 
@@ -115,9 +115,9 @@ def time_config(torch, seka, inputs, cfg, iters=10):
     Q, K, V = mk(Hq), mk(Hkv), mk(Hkv)
     O = torch.empty_like(Q)
     U = torch.from_numpy(inputs.orthonormal_bases(Hkv, M, D, r, 0, "bf16").view(np.int16)).view(torch.bfloat16).cuda()
-    recipe = {2: ("cover", 0.10, 0.10, 3), 4: ("cover", 0.10, 0.10, 3), 5: ("lengths", 8, 64, 512)}[cfg]
+    recipe = {2: ("cover", 0.10, 0.10, 3), 3: ("cover", 0.05, 0.20, 4), 4: ("cover", 0.10, 0.10, 3), 5: ("lengths", 8, 64, 512)}[cfg]
     mask = torch.from_numpy(inputs.span_mask(B, S, 0, recipe)[0]).cuda()
-    gain = [{2: 1.0, 4: 1.0, 5: 1.5}[cfg]] * Hkv
+    gain = [{2: 1.0, 3: 1.0, 4: 1.0, 5: 1.5}[cfg]] * Hkv
     w = None
     route_ms = None
     if M > 1:
@@ -133,6 +133,11 @@ def time_config(torch, seka, inputs, cfg, iters=10):
     if route_ms is not None:
         out["route_ms"] = round(route_ms, 4)
         out["route_GBps"] = round(B * S * Hq * D * 2 / route_ms / 1e6, 1)
+    # standalone key edit, out of place: reads K and writes K' once (algorithmic bytes 2 * |K|)
+    K2 = torch.empty_like(K)
+    edit_ms = event_time(torch, lambda: seka.seka_edit_keys(K, K2, U, gain, mask, w=w), iters, warm=10)
+    out["edit_keys_ms"] = round(edit_ms, 4)
+    out["edit_keys_GBps"] = round(2 * K.numel() * 2 / edit_ms / 1e6, 1)
     return out
 
 
@@ -218,7 +223,7 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     if args.extras:
-        out["other_configs"] = {f"cfg{c}": time_config(torch, seka, inputs, c) for c in (2, 4, 5)}
+        out["other_configs"] = {f"cfg{c}": time_config(torch, seka, inputs, c) for c in (2, 3, 4, 5)}
     del layers
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:

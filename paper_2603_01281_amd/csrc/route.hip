@@ -13,11 +13,17 @@ namespace seka {
 namespace {
 
 constexpr int kRouteThreads = 256;
-constexpr int kMaxChunks = 64;
+constexpr int kMaxChunks = 256;
+constexpr int kFinishThreads = 512;
 
-__host__ __device__ inline int route_chunks(int T) {
+// Chunks per (batch, KV head): enough workgroups for the whole chip (about 2048) even when B * Hkv is small,
+// at least 32 tokens per chunk, at most kMaxChunks partial sums for the second stage to add.
+__host__ __device__ inline int route_chunks(int T, int BH) {
+  int want = (2048 + BH - 1) / BH;
+  if (want < 16) want = 16;
+  if (want > kMaxChunks) want = kMaxChunks;
   int c = (T + 31) / 32;
-  return c < 1 ? 1 : (c > kMaxChunks ? kMaxChunks : c);
+  return c < 1 ? 1 : (c > want ? want : c);
 }
 
 template <typename T> struct Vec16;
@@ -62,13 +68,24 @@ __global__ __launch_bounds__(kRouteThreads) void route_partial_kernel(const T* _
 #pragma unroll
   for (int i = 0; i < VE; ++i) acc[i] = 0.f;
   const int nrows = max(0, tb - ta) * G;
-  for (int row = lane_row; row < nrows; row += RPP) {
-    const int t = ta + row / G, g = row % G;
-    const T* p = Q + (((size_t)b * S + t) * Hq + (size_t)h * G + g) * D + col * VE;
-    float v[VE];
-    Vec16<T>::load(p, v);
+  // four independent 16-byte loads per thread and turn keep enough bytes in flight
+  for (int row0 = lane_row; row0 < nrows; row0 += 4 * RPP) {
+    float v[4][VE];
 #pragma unroll
-    for (int i = 0; i < VE; ++i) acc[i] += v[i];
+    for (int u = 0; u < 4; ++u) {
+      const int row = row0 + u * RPP;
+      if (row < nrows) {
+        const int t = ta + row / G, g = row % G;
+        Vec16<T>::load(Q + (((size_t)b * S + t) * Hq + (size_t)h * G + g) * D + col * VE, v[u]);
+      } else {
+#pragma unroll
+        for (int i = 0; i < VE; ++i) v[u][i] = 0.f;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int i = 0; i < VE; ++i) acc[i] += v[u][i];
   }
 #pragma unroll
   for (int i = 0; i < VE; ++i) red[lane_row][col * VE + i] = acc[i];
@@ -81,18 +98,29 @@ __global__ __launch_bounds__(kRouteThreads) void route_partial_kernel(const T* _
   }
 }
 
-// grid = B*Hkv, block = 128.
+// grid = B*Hkv, block = kFinishThreads: thread (j, d) adds the partials of chunks j, j + NJ, ... in that order, then
+// the NJ sums are added in index order: a fixed order, whatever the launch.
 template <int D>
-__global__ __launch_bounds__(128) void route_finish_kernel(const float* __restrict__ workspace, int chunks, float inv_count,
+__global__ __launch_bounds__(kFinishThreads) void route_finish_kernel(const float* __restrict__ workspace, int chunks, float inv_count,
                                                            const float* __restrict__ proto, int Hkv, int M, int mode,
                                                            float tau, float* __restrict__ w_out) {
   __shared__ float qbar[D];
   __shared__ float dots[SEKA_MAX_EXPERTS];
   __shared__ float pnorm2[SEKA_MAX_EXPERTS];
+  constexpr int NJ = kFinishThreads / D;
+  __shared__ float part[NJ][D];
   const int bh = blockIdx.x, h = bh % Hkv;
+  {
+    const int d = threadIdx.x % D, j = threadIdx.x / D;
+    float s = 0.f;
+    for (int c = j; c < chunks; c += NJ) s += workspace[((size_t)bh * chunks + c) * D + d];
+    part[j][d] = s;
+  }
+  __syncthreads();
   if (threadIdx.x < D) {
     float s = 0.f;
-    for (int c = 0; c < chunks; ++c) s += workspace[((size_t)bh * chunks + c) * D + threadIdx.x];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) s += part[j][threadIdx.x];
     qbar[threadIdx.x] = s * inv_count;
   }
   __syncthreads();
@@ -138,12 +166,12 @@ __global__ __launch_bounds__(128) void route_finish_kernel(const float* __restri
 }  // namespace
 
 size_t route_workspace_bytes(int B, int Hkv, int D, int t0, int t1) {
-  return (size_t)B * Hkv * route_chunks(t1 - t0) * D * sizeof(float);
+  return (size_t)B * Hkv * route_chunks(t1 - t0, B * Hkv) * D * sizeof(float);
 }
 
 hipError_t launch_route(const void* Q, int B, int S, int Hq, int Hkv, int D, int dtype, const float* proto, int M,
                         int t0, int t1, int mode, float tau, float* w_out, void* workspace, hipStream_t s) {
-  const int chunks = route_chunks(t1 - t0);
+  const int chunks = route_chunks(t1 - t0, B * Hkv);
   const dim3 grid(chunks, B * Hkv);
   float* ws = static_cast<float*>(workspace);
   const float inv_count = 1.0f / ((float)(t1 - t0) * (float)(Hq / Hkv));
@@ -151,7 +179,7 @@ hipError_t launch_route(const void* Q, int B, int S, int Hq, int Hkv, int D, int
   do {                                                                                                               \
     hipLaunchKernelGGL((route_partial_kernel<T, DD>), grid, dim3(kRouteThreads), 0, s, static_cast<const T*>(Q), S,  \
                        Hq, Hkv, t0, t1, chunks, ws);                                                                 \
-    hipLaunchKernelGGL((route_finish_kernel<DD>), dim3(B * Hkv), dim3(128), 0, s, ws, chunks, inv_count, proto, Hkv, \
+    hipLaunchKernelGGL((route_finish_kernel<DD>), dim3(B * Hkv), dim3(kFinishThreads), 0, s, ws, chunks, inv_count, proto, Hkv, \
                        M, mode, tau, w_out);                                                                         \
   } while (0)
   if (dtype == SEKA_BF16) {

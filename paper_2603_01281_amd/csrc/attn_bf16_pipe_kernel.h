@@ -30,15 +30,17 @@
 
 namespace seka {
 
-// LDS beyond the two tile rings (steered kernels): the concatenated basis U_cat, the per-column coefficients and
-// one 64-bit highlight word per tile.  For a rank of at most 64 (nkr <= 2) U_cat is stored twice, once per
-// product of the edit, each copy in the order the MFMA operands are read (one conflict-free 16-byte read per
-// lane and operand); for larger ranks one row-major copy serves both products (transposing reads for the first).
+// LDS beyond the two tile rings (steered kernels): the edit's matrix operands, the per-column coefficients and
+// one 64-bit highlight word per tile.  Rank <= 32 (nkr == 1): U_cat stored twice, once per product of the
+// low-rank edit k' = k + U_cat (c . U_cat^T k).  Larger ranks: the dense D x D matrix g P = U_cat diag(c) U_cat^T,
+// built once per workgroup; at rank >= 64 one product with it moves no more operand bytes than the two low-rank
+// products and has no intermediate.  Either way the operands are stored in the order the MFMAs read them (one
+// conflict-free 16-byte LDS read per lane and operand).
 inline size_t attention_bf16_pipe_smem_bytes(int S, bool steer, int nkr) {
   size_t n = (size_t)2 * DMA_STAGES * DMA_TILE_BYTES;
   if (steer) {
     const int Rpad = 32 * nkr;
-    n += nkr <= 2 ? (size_t)2 * DMA_D * Rpad * 2 : (size_t)DMA_D * (Rpad + 8) * 2;
+    n += nkr == 1 ? (size_t)2 * DMA_D * Rpad * 2 : (size_t)DMA_D * DMA_D * 2;
     n += (size_t)Rpad * 4;
     n += (size_t)((S + DMA_BK - 1) / DMA_BK) * 8;
   }
@@ -93,12 +95,12 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   unsigned char* Kst = smem;                                     // [3][16 KB] swizzled K tiles
   unsigned char* Vst = smem + DMA_STAGES * TB;                   // [3][16 KB] swizzled V tiles
   constexpr int Rpad = 32 * NKR;
-  constexpr bool FRAG = NKR <= 2;          // operand-ordered copies of U_cat (see attention_bf16_pipe_smem_bytes)
-  constexpr int ULD = Rpad + 8;            // row-major copy: row stride in elements
-  uint16_t* UN = reinterpret_cast<uint16_t*>(smem + 2 * DMA_STAGES * TB);   // FRAG: U1 then U2; else [D][ULD]
-  uint16_t* U1 = UN;                       // operand (rb, s) of U_cat^T K^T: [2 NKR][4][64 lanes][8]
-  uint16_t* U2 = UN + D * Rpad;            // operand (s, half, kr) of U_cat Z: [4][2][NKR][64 lanes][8]
-  float* cvec = reinterpret_cast<float*>(UN + (FRAG ? (size_t)2 * D * Rpad : (size_t)D * ULD));   // [Rpad]
+  constexpr bool DENSE = NKR >= 2;         // edit with the dense matrix g P (see attention_bf16_pipe_smem_bytes)
+  uint16_t* UN = reinterpret_cast<uint16_t*>(smem + 2 * DMA_STAGES * TB);
+  uint16_t* U1 = UN;                       // low rank: operand (rb, s) of U_cat^T K^T: [2][4][64 lanes][8]
+  uint16_t* U2 = UN + D * Rpad;            // low rank: operand (s, half) of U_cat Z: [4][2][64 lanes][8]
+  uint16_t* AP = UN;                       // dense: operand (s_out, half, ks) of (g P) K^T: [4][2][4][64 lanes][8]
+  float* cvec = reinterpret_cast<float*>(UN + (DENSE ? (size_t)D * D : (size_t)2 * D * Rpad));   // [Rpad]
   unsigned long long* hlbits = reinterpret_cast<unsigned long long*>(cvec + Rpad);       // [tiles] (STEER)
 
   const uint16_t* __restrict__ Qg = static_cast<const uint16_t*>(a.Q);
@@ -191,23 +193,27 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     }
   }
 
-  // ---- steering set-up: U_cat, per-column coefficients, highlight bitmap ----
+  // ---- steering set-up: edit operands, per-column coefficients, highlight bitmap ----
   if (STEER && steer_on) {
     const int R = st.M * st.r;
-    if (R != Rpad) {
-      const int n16 = (FRAG ? 2 * D * Rpad : D * ULD) / 8;
-      for (int i = tid; i < n16; i += NT) reinterpret_cast<uint4*>(UN)[i] = make_uint4(0, 0, 0, 0);
-      __syncthreads();
-    }
     const uint16_t* Uh = static_cast<const uint16_t*>(st.U) + (size_t)h * st.M * D * st.r;
     const int r8 = st.r / 8;
     const int total = st.M * D * r8;
-    for (int idx = tid; idx < total; idx += NT) {
-      const int m = idx / (D * r8), rm = idx % (D * r8);
-      const int d = rm / r8, v = rm % r8;
-      const uint4 val = *reinterpret_cast<const uint4*>(Uh + ((size_t)m * D + d) * st.r + 8 * v);
-      const int r0 = m * st.r + 8 * v;              // concatenated column of the first of these 8 elements
-      if (FRAG) {
+    for (int r = tid; r < Rpad; r += NT) {
+      float c = 0.f;
+      if (r < R) c = gain * (st.w ? st.w[((size_t)b * a.Hkv + h) * st.M + r / st.r] : 1.f);
+      cvec[r] = c;
+    }
+    if (!DENSE) {
+      if (R != Rpad) {
+        for (int i = tid; i < 2 * D * Rpad / 8; i += NT) reinterpret_cast<uint4*>(UN)[i] = make_uint4(0, 0, 0, 0);
+        __syncthreads();
+      }
+      for (int idx = tid; idx < total; idx += NT) {
+        const int m = idx / (D * r8), rm = idx % (D * r8);
+        const int d = rm / r8, v = rm % r8;
+        const uint4 val = *reinterpret_cast<const uint4*>(Uh + ((size_t)m * D + d) * st.r + 8 * v);
+        const int r0 = m * st.r + 8 * v;              // concatenated column of the first of these 8 elements
         const uint16_t* e16 = reinterpret_cast<const uint16_t*>(&val);
         // first product: operand (rb, s), lane (g, j) holds U_cat[d = 32 s + 8 g + e][r = 16 rb + j], e = 0..7
         const int s1 = d >> 5, g1 = (d >> 3) & 3, e1 = d & 7;
@@ -216,23 +222,70 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
           const int r = r0 + i;
           U1[((((r >> 4) * 4 + s1) * 64) + g1 * 16 + (r & 15)) * 8 + e1] = e16[i];
         }
-        // second product: operand (s, half, kr), lane (g, j) holds U_cat[d = 32 s + 8 (j / 4) + 4 half + j % 4]
-        // [r = 32 kr + 16 (e / 4) + 4 g + e % 4], e = 0..7: four consecutive columns are four consecutive slots
+        // second product: operand (s, half), lane (g, j) holds U_cat[d = 32 s + 8 (j / 4) + 4 half + j % 4]
+        // [r = 16 (e / 4) + 4 g + e % 4], e = 0..7: four consecutive columns are four consecutive slots
         const int dl = d & 31, j2 = 4 * (dl >> 3) + (dl & 3), half2 = (dl >> 2) & 1;
 #pragma unroll
         for (int q = 0; q < 2; ++q) {
-          const int r = r0 + 4 * q, rl = r & 31;
-          uint16_t* dst = U2 + (((((s1 * 2 + half2) * NKR + (r >> 5)) * 64) + ((rl & 15) >> 2) * 16 + j2) * 8 + 4 * (rl >> 4));
+          const int rl = (r0 + 4 * q) & 31;
+          uint16_t* dst = U2 + ((((s1 * 2 + half2) * 64) + ((rl & 15) >> 2) * 16 + j2) * 8 + 4 * (rl >> 4));
           *reinterpret_cast<uint2*>(dst) = q == 0 ? make_uint2(val.x, val.y) : make_uint2(val.z, val.w);
         }
-      } else {
-        *reinterpret_cast<uint4*>(UN + (size_t)d * ULD + r0) = val;
       }
-    }
-    for (int r = tid; r < Rpad; r += NT) {
-      float c = 0.f;
-      if (r < R) c = gain * (st.w ? st.w[((size_t)b * a.Hkv + h) * st.M + r / st.r] : 1.f);
-      cvec[r] = c;
+    } else {
+      // Dense form.  U_cat (row d, r contiguous, zero-padded to Rpad columns) is staged in the third stage of
+      // the two tile rings, which no tile load touches before the main loop starts; 16-byte chunks of a row are
+      // swizzled so that sixteen consecutive rows can be read at one chunk index without bank conflicts.
+      constexpr int CPR = Rpad / 8;                    // chunks per row: 8 or 16
+      auto ustage = [&](int d, int chunk) __attribute__((always_inline)) -> unsigned char* {
+        const int sw = CPR == 16 ? (d & 15) : ((d >> 1) & 7);
+        const int off = d * (Rpad * 2) + 16 * (chunk ^ sw);
+        return off < TB ? Kst + 2 * TB + off : Vst + 2 * TB + (off - TB);
+      };
+      for (int idx = tid; idx < total; idx += NT) {
+        const int m = idx / (D * r8), rm = idx % (D * r8);
+        const int d = rm / r8, v = rm % r8;
+        *reinterpret_cast<uint4*>(ustage(d, (m * st.r) / 8 + v)) =
+            *reinterpret_cast<const uint4*>(Uh + ((size_t)m * D + d) * st.r + 8 * v);
+      }
+      const int padc = CPR - R / 8;                    // R is a multiple of 8
+      for (int idx = tid; idx < D * padc; idx += NT)
+        *reinterpret_cast<uint4*>(ustage(idx / padc, R / 8 + idx % padc)) = make_uint4(0, 0, 0, 0);
+      __syncthreads();
+      // T = (U_cat diag(c)) U_cat^T in 16 x 16 blocks; wave w computes the rows 16 w .. 16 w + 15.  The block
+      // element T[y][x] is stored where the edit expects (g P)[d_out = x][d' = y] (T is symmetric up to rounding).
+      const int j = lane & 15, g = lane >> 4;
+      for (int strip = wave; strip < D / 16; strip += NW) {
+        bf16x8 af[NKR];      // A operand: lane (row = 16 strip + j, k = r = 32 kk + 8 g + e), scaled by c_r
+#pragma unroll
+        for (int kk = 0; kk < NKR; ++kk) {
+          const bf16x8 u = *reinterpret_cast<const bf16x8*>(ustage(16 * strip + j, 4 * kk + g));
+          const f32x4 c0 = *reinterpret_cast<const f32x4*>(cvec + 32 * kk + 8 * g);
+          const f32x4 c1 = *reinterpret_cast<const f32x4*>(cvec + 32 * kk + 8 * g + 4);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            af[kk][e] = (__bf16)((float)u[e] * c0[e]);
+            af[kk][4 + e] = (__bf16)((float)u[4 + e] * c1[e]);
+          }
+        }
+#pragma unroll 2
+        for (int ct = 0; ct < D / 16; ++ct) {
+          f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+          for (int kk = 0; kk < NKR; ++kk) {
+            const bf16x8 bfr = *reinterpret_cast<const bf16x8*>(ustage(16 * ct + j, 4 * kk + g));
+            acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af[kk], bfr, acc, 0, 0, 0);
+          }
+          // this lane holds T[y = 16 strip + 4 g + i][x = 16 ct + j], i = 0..3
+          const int x = 16 * ct + j, xl = x & 31, y0 = 16 * strip + 4 * g;
+          const int frag = ((x >> 5) * 2 + ((xl >> 2) & 1)) * 4 + (y0 >> 5);           // (s_out, half, ks)
+          const int flane = 16 * ((y0 & 31) >> 3) + 4 * (xl >> 3) + (xl & 3);          // lane (g', j') of the edit
+          bf16x4 o4;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) o4[i] = (__bf16)acc[i];
+          *reinterpret_cast<uint2*>(AP + (frag * 64 + flane) * 8 + (y0 & 7)) = __builtin_bit_cast(uint2, o4);
+        }
+      }
     }
     // one 64-bit word per tile, one thread per tile: bit k = key 64 t + k is highlighted
     const uint8_t* mrow = st.mask + (size_t)b * S;
@@ -270,7 +323,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   };
 
   // Edit the highlighted 16-key blocks of the (swizzled) K tile at Kb: wave w < 4 owns block w.  What bounds the
-  // edit is LDS traffic for U_cat (every block reads all of it, twice), so the blocks are not split further.
+  // edit is LDS traffic for its matrix operands (every block reads all of them), so blocks are not split further.
   auto edit_tile = [&](unsigned char* Kb, unsigned long long bits) __attribute__((always_inline)) {
     // The lane index is re-derived behind an opaque copy so that none of the per-lane operand addresses below
     // is hoisted out of the tile loop: they would occupy registers the attention pipeline needs.
@@ -286,60 +339,50 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 #pragma unroll
     for (int s = 0; s < KS2; ++s) kreg[s] = *reinterpret_cast<const bf16x8*>(krow + 16 * ((4 * s + g) ^ j));
     const float mbit = ((bits16 >> j) & 1u) ? 1.f : 0.f;
-    // z^T = U_cat^T K^T (rows r, columns keys), scaled by the per-column coefficient and the key's mask bit
-    bf16x8 zb[NKR];
-    const uint16_t* ut = UN + (size_t)(8 * g + (j >> 2)) * ULD + 4 * (j & 3);      // row-major copy (not FRAG)
-#pragma unroll
-    for (int kr = 0; kr < NKR; ++kr) {
+    bf16x8 zb;
+    if (!DENSE) {
+      // z^T = U_cat^T K^T (rows r, columns keys), scaled by the per-column coefficient and the key's mask bit
       float zc[8];
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
-        const int rb = 2 * kr + half;
         f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};   // two chains: even and odd slices of d
 #pragma unroll
         for (int s = 0; s < KS2; ++s) {
-          bf16x8 ua;
-          if (FRAG) {
-            ua = *reinterpret_cast<const bf16x8*>(U1 + ((rb * 4 + s) * 64 + ln) * 8);
-          } else {
-            const uint16_t* p = ut + (size_t)(32 * s) * ULD + 16 * rb;
-            ua = dma_read_tr_pair(reinterpret_cast<const unsigned char*>(p),
-                                  reinterpret_cast<const unsigned char*>(p + 4 * ULD));
-          }
+          const bf16x8 ua = *reinterpret_cast<const bf16x8*>(U1 + ((half * 4 + s) * 64 + ln) * 8);
           acc[s & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua, kreg[s], acc[s & 1], 0, 0, 0);
         }
-        const f32x4 c4 = *reinterpret_cast<const f32x4*>(cvec + 16 * rb + 4 * g);
+        const f32x4 c4 = *reinterpret_cast<const f32x4*>(cvec + 16 * half + 4 * g);
 #pragma unroll
         for (int i = 0; i < 4; ++i) zc[4 * half + i] = (acc[0][i] + acc[1][i]) * (c4[i] * mbit);
       }
-      bf16x8 z;   // next B operand: slot e <-> r = 32 kr + 16 (e / 4) + 4 g + e % 4
+      // next B operand: slot e <-> r = 16 (e / 4) + 4 g + e % 4
 #pragma unroll
-      for (int e = 0; e < 8; ++e) z[e] = (__bf16)zc[e];
-      zb[kr] = z;
+      for (int e = 0; e < 8; ++e) zb[e] = (__bf16)zc[e];
     }
-    // k' = k + U_cat z: output rows d permuted so that each result lands in the lane holding that element of k
+    // k' = k + U_cat z (low rank) or k + mask (g P) k (dense): output rows d are permuted so that each result
+    // lands in the lane that holds that element of k
 #pragma unroll
     for (int s = 0; s < KS2; ++s) {
       float outv[8];
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        if (!DENSE) {
+          const bf16x8 ua = *reinterpret_cast<const bf16x8*>(U2 + ((s * 2 + half) * 64 + ln) * 8);
+          const f32x4 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua, zb, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
 #pragma unroll
-        for (int kr = 0; kr < NKR; ++kr) {
-          bf16x8 ua;
-          if (FRAG) {
-            ua = *reinterpret_cast<const bf16x8*>(U2 + (((s * 2 + half) * NKR + kr) * 64 + ln) * 8);
-          } else {
-            const int d_row = 32 * s + 8 * (j >> 2) + 4 * half + (j & 3);
-            const uint16_t* p = UN + (size_t)d_row * ULD + 32 * kr + 4 * g;
-            const bf16x4 u0 = *reinterpret_cast<const bf16x4*>(p);
-            const bf16x4 u1 = *reinterpret_cast<const bf16x4*>(p + 16);
-            ua = __builtin_shufflevector(u0, u1, 0, 1, 2, 3, 4, 5, 6, 7);
+          for (int i = 0; i < 4; ++i) outv[4 * half + i] = (float)kreg[s][4 * half + i] + acc[i];
+        } else {
+          f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
+#pragma unroll
+          for (int ks = 0; ks < KS2; ++ks) {
+            const bf16x8 ua = *reinterpret_cast<const bf16x8*>(AP + (((s * 2 + half) * 4 + ks) * 64 + ln) * 8);
+            acc[ks & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua, kreg[ks], acc[ks & 1], 0, 0, 0);
           }
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua, zb[kr], acc, 0, 0, 0);
-        }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) outv[4 * half + i] = (float)kreg[s][4 * half + i] + acc[i];
+          for (int i = 0; i < 4; ++i)
+            outv[4 * half + i] = (float)kreg[s][4 * half + i] + mbit * (acc[0][i] + acc[1][i]);
+          __builtin_amdgcn_sched_barrier(0);     // keeps the operand reads of later row groups from piling up in registers
+        }
       }
       bf16x8 o;
 #pragma unroll
@@ -555,8 +598,9 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 
   // One software-pipelined step: the S^T block at LDS offset KOFF is produced into `next` while the softmax of
   // `cur` runs on the vector ALU; then the PV products of `cur` (V rows at LDS offset VOFF).
+  // The LDS offsets are std::integral_constant in the main loop (they become immediates) and int elsewhere.
   auto step = [&](auto koff_c, auto voff_c, f32x16 (&cur)[RPW], f32x16 (&next)[RPW]) __attribute__((always_inline)) {
-    constexpr int KOFF = decltype(koff_c)::value, VOFF = decltype(voff_c)::value;
+    const int KOFF = koff_c, VOFF = voff_c;
     constexpr int NM = (KS / 2) * RPW;            // MFMAs per half of the S^T block
     bf16x8 pb[RPW][2];
     float mfull[RPW];
@@ -625,20 +669,30 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
       hot(integral_constant<int, 2>{}, t); if (++t == t_hot) break;
     }
   }
-  // ---- the remaining tiles, unpipelined: up to two before the wave's last tile, the last tile (causal mask),
-  // then idle turns while other waves of the workgroup finish ----
+#ifdef SEKA_CYCLE_PROBE
+  const unsigned long long prb_tail = __builtin_amdgcn_s_memtime();
+#endif
+  // ---- up to two more full tiles before the wave's last one: same pipelined step, ring stage known at run time ----
+#pragma nounroll
+  for (; t < tw_last; ++t) {
+    top(std::false_type{}, IC0{}, t);
+    const int off = (t % 3) * TB, offn = ((t + 1) % 3) * TB;
+    step(off + 32 * 256, off, sc0, sc1);
+    step(offn, off + 32 * 256, sc1, sc0);
+    bottom(std::false_type{}, t);
+  }
+  // ---- the wave's last tile (causal mask, nothing further to score), then idle turns while other waves finish ----
 #pragma nounroll
   for (; t < ntiles; ++t) {
     top(std::false_type{}, IC0{}, t);
-    if (t <= tw_last) {
+    if (t == tw_last) {
       const int off = (t % 3) * TB;
-      const bool diag = t == tw_last;
       bf16x8 pb[RPW][2];
       qk_part(IC0{}, ICK{}, off + 32 * 256, sc1);
 #pragma unroll
       for (int rp = 0; rp < RPW; ++rp) {
         pipe_mfma_result_guard(sc0[rp]);
-        if (diag) causal_mask(t * BK, rp, sc0[rp]);
+        causal_mask(t * BK, rp, sc0[rp]);
         raise_reference(rp, block_max(sc0[rp]));
         block_exp(rp, sc0[rp], pb[rp]);
       }
@@ -646,12 +700,11 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 #pragma unroll
       for (int rp = 0; rp < RPW; ++rp) {
         pipe_mfma_result_guard(sc1[rp]);
-        if (diag) causal_mask(t * BK + 32, rp, sc1[rp]);
+        causal_mask(t * BK + 32, rp, sc1[rp]);
         raise_reference(rp, block_max(sc1[rp]));
         block_exp(rp, sc1[rp], pb[rp]);
       }
       pv_half(off + 32 * 256, pb);
-      if (!diag) qk_part(IC0{}, ICK{}, ((t + 1) % 3) * TB, sc0);     // K(t+1) landed (and was edited) an iteration ago
     }
     bottom(std::false_type{}, t);
   }
@@ -684,6 +737,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
         dp[4] = (float)prb_bar;                                          // waiting at the per-tile barrier
         dp[5] = (float)prb_edit;                                         // key edits incl. their barrier
         dp[6] = (float)prb_n;
+        dp[7] = (float)(prb_tail - prb_start);                           // prologue edits and pipelined iterations
       }
       if (false)
 #endif

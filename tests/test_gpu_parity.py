@@ -96,6 +96,14 @@ BF16_CASES = {
     "D64": dict(cfg=2, S=500, Hq=8, Hkv=2, D=64, r=16),
     "rank_pad_r8": dict(cfg=2, S=320, Hq=4, Hkv=1, r=8),
     "rank_r48": dict(cfg=2, S=320, Hq=4, Hkv=1, r=48),
+    # mask rows of batch entries > 0 start at odd addresses (byte-wise mask scan), ragged last tile
+    "B2_odd_S": dict(cfg=3, S=333, B=2, Hq=8, Hkv=2, layer=10),
+    # per-head gains: negative, zero (head not steered), positive
+    "mixed_gains": dict(cfg=2, S=400, Hq=12, Hkv=3, gain=[-0.5, 0.0, 1.25]),
+    # two experts blended by fixed routing weights are covered by test_bf16_adaseka_routed; here rank 64 in one expert
+    "rank_r64_G4": dict(cfg=5, S=700, Hq=8, Hkv=2),
+    # more than 64 key tiles: the per-workgroup tile summary is reloaded
+    "many_tiles": dict(cfg=2, S=4500, Hq=4, Hkv=1, mask_recipe=("lengths", 6, 40, 300)),
 }
 
 

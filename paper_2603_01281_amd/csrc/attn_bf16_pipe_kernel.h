@@ -526,6 +526,14 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   const unsigned long long prb_rstart = __builtin_amdgcn_s_memrealtime();
 #endif
   unsigned long long anyw = 0ull;      // bit i: tile 64 (t / 64) + i holds a highlighted key (0 when not steering)
+  // Next tile index at which the loop has something to do besides attention: a tile with highlighted keys, or
+  // the start of the next group of 64 tiles (summary reload).  Scalar; the loop compares one integer per tile.
+  auto next_event = [&](int tile) __attribute__((always_inline)) -> int {     // first event strictly after `tile`
+    const unsigned sh = tile & 63;
+    const unsigned long long rest = sh == 63u ? 0ull : anyw >> (sh + 1);
+    return rest != 0ull ? tile + 1 + __builtin_ctzll(rest) : (tile | 63) + 1;
+  };
+  int tile_evt = 0x7fffffff;
   if (STEER) {
     anyw = any_word(0);
     if (anyw & 3ull) {
@@ -533,6 +541,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
       if (anyw & 2ull) edit_tile(Kst + TB, hlbits[1]);
       dma_barrier();
     }
+    tile_evt = next_event(1);
   }
 
   f32x16 sc0[RPW], sc1[RPW];   // scores of keys 0..31 / 32..63 of the current tile, per row block
@@ -576,11 +585,12 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     dma_barrier();
 #endif
     if (STEER) {
-      // one scalar branch in the common case; tiles past the end and unsteered heads have no bit set
+      // one scalar compare in the common case; tiles past the end and unsteered heads have no bit set
       const int tn = t + 2;
-      const unsigned sh = tn & 63;
-      if (__builtin_expect((((anyw >> sh) & 1ull) != 0ull) | (sh == 0u), 0)) {
+      if (__builtin_expect(tn == tile_evt, 0)) {
+        const unsigned sh = tn & 63;
         if (sh == 0u) anyw = any_word(tn);
+        tile_evt = next_event(tn);
         if ((anyw >> sh) & 1ull) {
 #ifdef SEKA_CYCLE_PROBE
           const unsigned long long c0 = __builtin_amdgcn_s_memtime();

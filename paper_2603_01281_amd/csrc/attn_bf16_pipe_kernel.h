@@ -340,6 +340,12 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     for (int s = 0; s < KS2; ++s) kreg[s] = *reinterpret_cast<const bf16x8*>(krow + 16 * ((4 * s + g) ^ j));
     const float mbit = ((bits16 >> j) & 1u) ? 1.f : 0.f;
     bf16x8 zb;
+    bf16x8 u2[DENSE ? 1 : 2 * KS2];      // low rank: all operands of the second product, requested up front so that
+    if (!DENSE) {                        // the product runs back to back instead of one LDS round trip per slice
+#pragma unroll
+      for (int i = 0; i < KS2; ++i) u2[i] = *reinterpret_cast<const bf16x8*>(U2 + (i * 64 + ln) * 8);
+      __builtin_amdgcn_sched_barrier(0);
+    }
     if (!DENSE) {
       // z^T = U_cat^T K^T (rows r, columns keys), scaled by the per-column coefficient and the key's mask bit
       float zc[8];
@@ -358,6 +364,9 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
       // next B operand: slot e <-> r = 16 (e / 4) + 4 g + e % 4
 #pragma unroll
       for (int e = 0; e < 8; ++e) zb[e] = (__bf16)zc[e];
+#pragma unroll
+      for (int i = KS2; i < 2 * KS2; ++i) u2[i] = *reinterpret_cast<const bf16x8*>(U2 + (i * 64 + ln) * 8);
+      __builtin_amdgcn_sched_barrier(0);
     }
     // k' = k + U_cat z (low rank) or k + mask (g P) k (dense): output rows d are permuted so that each result
     // lands in the lane that holds that element of k
@@ -367,8 +376,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
         if (!DENSE) {
-          const bf16x8 ua = *reinterpret_cast<const bf16x8*>(U2 + ((s * 2 + half) * 64 + ln) * 8);
-          const f32x4 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua, zb, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+          const f32x4 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(u2[s * 2 + half], zb, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
 #pragma unroll
           for (int i = 0; i < 4; ++i) outv[4 * half + i] = (float)kreg[s][4 * half + i] + acc[i];
         } else {

@@ -186,33 +186,102 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     const bool ok = qi < S;
     const uint16_t* qp = Qg + (((size_t)b * S + (ok ? qi : 0)) * a.Hq + hq) * D + 8 * hf;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (ok) v = *reinterpret_cast<const uint4*>(qp + 16 * ks);
-      qf[rp][ks] = __builtin_bit_cast(bf16x8, v);
-    }
+    for (int ks = 0; ks < KS; ++ks)     // rows past the end read row 0 (finite data, results never stored):
+      qf[rp][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + 16 * ks));   // no branch, no wait here
   }
 
   // ---- steering set-up: edit operands, per-column coefficients, highlight bitmap ----
+  // Every global load of the set-up (mask bytes, U_cat, routing weights) is issued before the first of them is
+  // waited for, with addresses clamped into range instead of branches around the loads: one memory round trip.
   if (STEER && steer_on) {
     const int R = st.M * st.r;
     const uint16_t* Uh = static_cast<const uint16_t*>(st.U) + (size_t)h * st.M * D * st.r;
     const int r8 = st.r / 8;
-    const int total = st.M * D * r8;
-    for (int r = tid; r < Rpad; r += NT) {
-      float c = 0.f;
-      if (r < R) c = gain * (st.w ? st.w[((size_t)b * a.Hkv + h) * st.M + r / st.r] : 1.f);
-      cvec[r] = c;
+    const int total = st.M * D * r8;                  // 16-byte pieces of U_cat
+    constexpr int UB = 4;                             // pieces per thread and turn
+
+    // (1) mask bytes of tile `tid` (first turn of the bitmap loop), if the fast form applies
+    const uint8_t* mrow = st.mask + (size_t)b * S;
+    const int nfull = S / BK;
+    const bool wide = (reinterpret_cast<uintptr_t>(mrow) & 15) == 0 && nfull > 0;
+    uint4 mv0[BK / 16];
+    if (wide) {
+      const uint4* mp = reinterpret_cast<const uint4*>(mrow + (size_t)min(tid, nfull - 1) * BK);
+#pragma unroll
+      for (int q = 0; q < BK / 16; ++q) mv0[q] = mp[q];
     }
-    if (!DENSE) {
-      if (R != Rpad) {
-        for (int i = tid; i < 2 * D * Rpad / 8; i += NT) reinterpret_cast<uint4*>(UN)[i] = make_uint4(0, 0, 0, 0);
-        __syncthreads();
+    // (2) first turn of U_cat.  Piece idx = (expert m, row d, 8-column group v); the divisions by run-time
+    // constants are done in floating point (exact for these small operands: idx < 64 K, quotients < 2 K).
+    const float inv_dr8 = 1.f / (float)(D * r8), inv_r8 = 1.f / (float)r8;
+    auto split = [&](int idx, int& m, int& d, int& v) __attribute__((always_inline)) {
+      m = (int)(((float)idx + 0.5f) * inv_dr8);
+      const int rm = idx - m * (D * r8);
+      d = (int)(((float)rm + 0.5f) * inv_r8);
+      v = rm - d * r8;
+    };
+    uint4 uv[UB];
+    int um[UB], ud[UB], uc[UB];
+#pragma unroll
+    for (int k = 0; k < UB; ++k) {
+      uv[k] = make_uint4(0, 0, 0, 0);
+      um[k] = ud[k] = uc[k] = 0;
+      if (k * NT < total) {                          // workgroup-uniform
+        split(min(tid + k * NT, total - 1), um[k], ud[k], uc[k]);
+        uv[k] = *reinterpret_cast<const uint4*>(Uh + ((size_t)um[k] * D + ud[k]) * st.r + 8 * uc[k]);
       }
-      for (int idx = tid; idx < total; idx += NT) {
-        const int m = idx / (D * r8), rm = idx % (D * r8);
-        const int d = rm / r8, v = rm % r8;
-        const uint4 val = *reinterpret_cast<const uint4*>(Uh + ((size_t)m * D + d) * st.r + 8 * v);
+    }
+    // (3) routing weight of column `tid`
+    float cw = 1.f;
+    if (st.w) cw = st.w[((size_t)b * a.Hkv + h) * st.M + min(tid, R - 1) / st.r];
+
+    auto bits_of = [&](const uint4 (&mv)[BK / 16]) __attribute__((always_inline)) -> unsigned long long {
+      unsigned long long bits = 0ull;
+#pragma unroll
+      for (int q = 0; q < BK / 16; ++q) {
+        const uint32_t x4[4] = {mv[q].x, mv[q].y, mv[q].z, mv[q].w};
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          // non-zero test of the four bytes of x, gathered into four adjacent bits
+          const uint32_t x = x4[w];
+          const uint32_t y = ((x | ((x & 0x7f7f7f7fu) + 0x7f7f7f7fu)) & 0x80808080u) >> 7;
+          const uint32_t nib = ((y * 0x00204081u) >> 21) & 0xfu;
+          bits |= (unsigned long long)nib << (16 * q + 4 * w);
+        }
+      }
+      return bits;
+    };
+    // one 64-bit word per tile, one thread per tile: bit k = key 64 t + k is highlighted
+    for (int t = tid; t < ntiles; t += NT) {
+      unsigned long long bits = 0ull;
+      if (wide && t < nfull) {
+        if (t == tid) {
+          bits = bits_of(mv0);
+        } else {
+          uint4 mv[BK / 16];
+          const uint4* mp = reinterpret_cast<const uint4*>(mrow + (size_t)t * BK);
+#pragma unroll
+          for (int q = 0; q < BK / 16; ++q) mv[q] = mp[q];
+          bits = bits_of(mv);
+        }
+      } else {
+        for (int k = 0; k < BK; ++k)
+          if (t * BK + k < S && mrow[(size_t)t * BK + k] != 0) bits |= 1ull << k;
+      }
+      hlbits[t] = bits;
+    }
+    if (tid < Rpad) cvec[tid] = tid < R ? gain * cw : 0.f;        // Rpad <= 128 < NT
+
+    // where a 16-byte piece of U_cat goes
+    constexpr int CPR = Rpad / 8;                    // dense form: chunks per staged row, 8 or 16
+    auto ustage = [&](int d, int chunk) __attribute__((always_inline)) -> unsigned char* {
+      const int sw = CPR == 16 ? (d & 15) : ((d >> 1) & 7);
+      const int off = d * (Rpad * 2) + 16 * (chunk ^ sw);
+      return off < TB ? Kst + 2 * TB + off : Vst + 2 * TB + (off - TB);
+    };
+    auto place = [&](int m, int d, int v, const uint4 val) __attribute__((always_inline)) {
+      if (DENSE) {
+        *reinterpret_cast<uint4*>(ustage(d, (m * st.r) / 8 + v)) = val;
+      } else {
         const int r0 = m * st.r + 8 * v;              // concatenated column of the first of these 8 elements
         const uint16_t* e16 = reinterpret_cast<const uint16_t*>(&val);
         // first product: operand (rb, s), lane (g, j) holds U_cat[d = 32 s + 8 g + e][r = 16 rb + j], e = 0..7
@@ -232,22 +301,23 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
           *reinterpret_cast<uint2*>(dst) = q == 0 ? make_uint2(val.x, val.y) : make_uint2(val.z, val.w);
         }
       }
-    } else {
+    };
+    if (!DENSE && R != Rpad) {
+      for (int i = tid; i < 2 * D * Rpad / 8; i += NT) reinterpret_cast<uint4*>(UN)[i] = make_uint4(0, 0, 0, 0);
+      __syncthreads();
+    }
+#pragma unroll
+    for (int k = 0; k < UB; ++k)
+      if (tid + k * NT < total) place(um[k], ud[k], uc[k], uv[k]);
+    for (int idx = tid + UB * NT; idx < total; idx += NT) {        // further turns (large rank and few waves only)
+      int m, d, v;
+      split(idx, m, d, v);
+      place(m, d, v, *reinterpret_cast<const uint4*>(Uh + ((size_t)m * D + d) * st.r + 8 * v));
+    }
+    if (DENSE) {
       // Dense form.  U_cat (row d, r contiguous, zero-padded to Rpad columns) is staged in the third stage of
       // the two tile rings, which no tile load touches before the main loop starts; 16-byte chunks of a row are
       // swizzled so that sixteen consecutive rows can be read at one chunk index without bank conflicts.
-      constexpr int CPR = Rpad / 8;                    // chunks per row: 8 or 16
-      auto ustage = [&](int d, int chunk) __attribute__((always_inline)) -> unsigned char* {
-        const int sw = CPR == 16 ? (d & 15) : ((d >> 1) & 7);
-        const int off = d * (Rpad * 2) + 16 * (chunk ^ sw);
-        return off < TB ? Kst + 2 * TB + off : Vst + 2 * TB + (off - TB);
-      };
-      for (int idx = tid; idx < total; idx += NT) {
-        const int m = idx / (D * r8), rm = idx % (D * r8);
-        const int d = rm / r8, v = rm % r8;
-        *reinterpret_cast<uint4*>(ustage(d, (m * st.r) / 8 + v)) =
-            *reinterpret_cast<const uint4*>(Uh + ((size_t)m * D + d) * st.r + 8 * v);
-      }
       const int padc = CPR - R / 8;                    // R is a multiple of 8
       for (int idx = tid; idx < D * padc; idx += NT)
         *reinterpret_cast<uint4*>(ustage(idx / padc, R / 8 + idx % padc)) = make_uint4(0, 0, 0, 0);
@@ -268,7 +338,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
             af[kk][4 + e] = (__bf16)((float)u[4 + e] * c1[e]);
           }
         }
-#pragma unroll 2
+#pragma unroll
         for (int ct = 0; ct < D / 16; ++ct) {
           f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -286,32 +356,6 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
           *reinterpret_cast<uint2*>(AP + (frag * 64 + flane) * 8 + (y0 & 7)) = __builtin_bit_cast(uint2, o4);
         }
       }
-    }
-    // one 64-bit word per tile, one thread per tile: bit k = key 64 t + k is highlighted
-    const uint8_t* mrow = st.mask + (size_t)b * S;
-    const bool wide = (reinterpret_cast<uintptr_t>(mrow) & 15) == 0;
-    for (int t = tid; t < ntiles; t += NT) {
-      unsigned long long bits = 0ull;
-      if (wide && t * BK + BK <= S) {
-        const uint4* mp = reinterpret_cast<const uint4*>(mrow + (size_t)t * BK);
-#pragma unroll
-        for (int q = 0; q < BK / 16; ++q) {
-          const uint4 mv = mp[q];
-          const uint32_t x4[4] = {mv.x, mv.y, mv.z, mv.w};
-#pragma unroll
-          for (int w = 0; w < 4; ++w) {
-            // non-zero test of the four bytes of x, gathered into four adjacent bits
-            const uint32_t x = x4[w];
-            const uint32_t y = ((x | ((x & 0x7f7f7f7fu) + 0x7f7f7f7fu)) & 0x80808080u) >> 7;
-            const uint32_t nib = ((y * 0x00204081u) >> 21) & 0xfu;
-            bits |= (unsigned long long)nib << (16 * q + 4 * w);
-          }
-        }
-      } else {
-        for (int k = 0; k < BK; ++k)
-          if (t * BK + k < S && mrow[(size_t)t * BK + k] != 0) bits |= 1ull << k;
-      }
-      hlbits[t] = bits;
     }
   }
   // Which of the 64 tiles [tile0, tile0 + 64) hold a highlighted key: kept in scalar registers so that the common
@@ -522,6 +566,9 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   const bool wave_rows_exist = qw < S;
   const int tw_last = wave_rows_exist ? min(ntiles - 1, (qw + WR - 1) / BK) : -1;   // last tile this wave computes on
 
+#ifdef SEKA_CYCLE_PROBE
+  const unsigned long long prb_issued = __builtin_amdgcn_s_memtime();
+#endif
   // ---- prologue: wait for the first tiles, edit K(0) and K(1), first block of S^T ----
   dma_wait_vmcnt<0>();   // also covers the Q, U and mask loads issued after the tile loads
 #pragma unroll
@@ -755,6 +802,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
         dp[4] = (float)prb_bar;                                          // waiting at the per-tile barrier
         dp[5] = (float)prb_edit;                                         // key edits incl. their barrier
         dp[6] = (float)prb_n;
+        dp[8] = (float)(prb_issued - prb_entry);                         // set-up until every load has been issued
         dp[7] = (float)(prb_tail - prb_start);                           // prologue edits and pipelined iterations
       }
       if (false)

@@ -15,6 +15,10 @@ What is written out here, in the order the paper states it:
 * Eq. 2            P = U_{:, :k} U_{:, :k}^T                      -> projector
 * Sec. 3.3         P_dynamic = sum_m alpha_m U_m U_m^T            -> blended_projector
 * Sec. 2 / Alg. 2  k' = k + g * P k on highlighted tokens only    -> edit_keys
+* Eq. 2 + Eq. 4    k' = k + (g+ P+ k + g- P- k) / 2, P- from the trailing singular vectors
+                                                                  -> edit_keys_eq4 (and eq4_as_low_rank:
+                                                                     the same edit as a scaled key plus a
+                                                                     signed low-rank update, fed to edit_keys)
 * Sec. 2           Attn(i, j) = q_i . k_j / sqrt(d_k), causal softmax, weighted sum of V
                                                                   -> causal_attention
 * Eq. 6            alpha_m = sum_k (q.u_m^(k)) sigma_m^(k) / max_m |.|   -> route_eq6
@@ -22,8 +26,10 @@ What is written out here, in the order the paper states it:
                                                                   -> route_softmax_cos
 
 Pins (tests/test_oracle_*.py): closed form of Appendix C, score-side form of
-Eq. 5, query-side form (Sec. 2), library scaled-dot-product attention, and
-brute-force scalar loops on tiny shapes.  No function here is unpinned.
+Eq. 5, query-side form (Sec. 2), library scaled-dot-product attention,
+brute-force scalar loops on tiny shapes, and for Eq. 4 the agreement of its two
+independent forms plus its special cases (g- = 0, k- = d, hand-worked 2-d case).
+No function here is unpinned.
 """
 import numpy as np
 
@@ -51,11 +57,12 @@ def blended_projector(U_bank, alpha):
     return P
 
 
-def edit_keys(K, U, gain, mask, w=None):
-    """Hook of Algorithms 1/2: K[b,t,h,:] += g_h * P_{b,h} K[b,t,h,:] where m[b,t] != 0.
+def edit_keys(K, U, gain, mask, w=None, key_scale=None):
+    """Hook of Algorithms 1/2: K[b,t,h,:] = a_h * K[b,t,h,:] + g_h * P_{b,h} K[b,t,h,:] where m[b,t] != 0.
 
     K[B,T,H,d]; U[H,M,d,r]; gain[H] (0 = head not selected, Sec. 3.4);
-    mask[B,T]; w[B,H,M] routing coefficients or None for all-ones (SEKA).
+    mask[B,T]; w[B,H,M] routing coefficients or None for all-ones (SEKA);
+    key_scale[H] = a_h or None for 1 (a_h != 1 only arises from Eq. 4 with g- != 0, see eq4_as_low_rank).
     Returns a new array; rows that are not highlighted are copied untouched.
     """
     K = np.asarray(K, dtype=_F)
@@ -75,8 +82,56 @@ def edit_keys(K, U, gain, mask, w=None):
             P = blended_projector(U[h], alpha)
             k = K[b, hl, h, :]                      # [n, d], one key per row
             delta = g * (k @ P.T)                   # row form of g * P k
-            K_out[b, hl, h, :] = k + delta
+            a = 1.0 if key_scale is None else float(key_scale[h])
+            K_out[b, hl, h, :] = a * k + delta
     return K_out
+
+
+def edit_keys_eq4(K, U_pos, U_neg, k_pos, k_neg, g_pos, g_neg, mask):
+    """Eq. 2 and Eq. 4 written out: k' = k + (g+ P+ k + g- P- k) / 2 on highlighted tokens, with
+    P+ = U+[:, :k+] U+[:, :k+]^T (leading singular vectors) and P- = U-[:, k-:] U-[:, k-:]^T (trailing ones).
+
+    K[B,T,H,d]; U_pos, U_neg [H,d,d] full sets of left singular vectors (orthogonal matrices);
+    k_pos, k_neg [H] integers; g_pos, g_neg scalars or [H]; mask[B,T].
+    """
+    K = np.asarray(K, dtype=_F)
+    B, T, H, d = K.shape
+    gp = np.broadcast_to(np.asarray(g_pos, dtype=_F), (H,))
+    gn = np.broadcast_to(np.asarray(g_neg, dtype=_F), (H,))
+    K_out = K.copy()
+    for h in range(H):
+        Up = np.asarray(U_pos[h], dtype=_F)[:, :int(k_pos[h])]
+        Un = np.asarray(U_neg[h], dtype=_F)[:, int(k_neg[h]):]
+        P_pos = Up @ Up.T
+        P_neg = Un @ Un.T
+        for b in range(B):
+            hl = np.flatnonzero(np.asarray(mask[b]) != 0)
+            k = K[b, hl, h, :]
+            K_out[b, hl, h, :] = k + (gp[h] * (k @ P_pos.T) + gn[h] * (k @ P_neg.T)) / 2.0
+    return K_out
+
+
+def eq4_as_low_rank(U_pos, U_neg, k_pos, k_neg, g_pos, g_neg, B):
+    """Eq. 4 in the form the hook takes.  Because U- is orthogonal, its trailing columns project onto the
+    complement of its leading ones: P- = I - U-[:, :k-] U-[:, :k-]^T, so
+        k' = (1 + g-/2) k + (g+/2) U+[:, :k+] U+[:, :k+]^T k - (g-/2) U-[:, :k-] U-[:, :k-]^T k,
+    i.e. two "experts" per head (leading k+ columns of U+, leading k- columns of U-, zero-padded to one
+    width r = max(k+, k-) rounded up to a multiple of 8), gain 1, coefficients (g+/2, -g-/2), key scale 1 + g-/2.
+    Returns U[H,2,d,r], gain[H], w[B,H,2], key_scale[H].
+    """
+    H, d, _ = np.asarray(U_pos).shape
+    gp = np.broadcast_to(np.asarray(g_pos, dtype=_F), (H,))
+    gn = np.broadcast_to(np.asarray(g_neg, dtype=_F), (H,))
+    r = int(max(max(int(x) for x in k_pos), max(int(x) for x in k_neg), 1))
+    r = (r + 7) // 8 * 8
+    U = np.zeros((H, 2, d, r), dtype=_F)
+    for h in range(H):
+        U[h, 0, :, :int(k_pos[h])] = np.asarray(U_pos[h], dtype=_F)[:, :int(k_pos[h])]
+        U[h, 1, :, :int(k_neg[h])] = np.asarray(U_neg[h], dtype=_F)[:, :int(k_neg[h])]
+    w = np.zeros((B, H, 2), dtype=_F)
+    w[:, :, 0] = gp / 2.0
+    w[:, :, 1] = -gn / 2.0
+    return U, np.ones(H, dtype=_F), w, 1.0 + gn / 2.0
 
 
 def causal_attention(Q, K, V, scale=None):
@@ -110,9 +165,9 @@ def causal_attention(Q, K, V, scale=None):
     return O, LSE
 
 
-def steered_attention(Q, K, V, U, gain, mask, w=None, scale=None):
+def steered_attention(Q, K, V, U, gain, mask, w=None, scale=None, key_scale=None):
     """Edited keys first (materialised), then ordinary causal attention on them."""
-    K_edit = edit_keys(K, U, gain, mask, w)
+    K_edit = edit_keys(K, U, gain, mask, w, key_scale)
     return causal_attention(Q, K_edit, V, scale)
 
 

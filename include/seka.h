@@ -68,6 +68,12 @@ typedef struct {
                              head is not selected for steering (paper Sec. 3.4)                */
   const uint8_t* mask;    /* dev [B, S]: nonzero = highlighted token (Algorithm 1, "if m_{b,t}
                              = 1"); shared by all heads                                        */
+  const float* key_scale; /* host [Hkv] fp32 or NULL for all ones: a of k' = a k + g P k on
+                             highlighted tokens of steered heads (gain != 0).  Eq. 4 with a
+                             negative-side gain is this form: its projector onto the trailing
+                             singular vectors is I minus the projector onto the leading ones,
+                             so k' = (1 + g-/2) k + (g+/2) P+ k - (g-/2) P-lead k: two experts
+                             with coefficients w = (g+/2, -g-/2), gain 1, key_scale 1 + g-/2  */
 } seka_steer;
 
 /*

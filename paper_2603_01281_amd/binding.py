@@ -34,7 +34,8 @@ class seka_shape(ctypes.Structure):
 
 class seka_steer(ctypes.Structure):
     _fields_ = [("M", ctypes.c_int32), ("r", ctypes.c_int32), ("U", ctypes.c_void_p), ("w", ctypes.c_void_p),
-                ("gain", ctypes.POINTER(ctypes.c_float)), ("mask", ctypes.c_void_p)]
+                ("gain", ctypes.POINTER(ctypes.c_float)), ("mask", ctypes.c_void_p),
+                ("key_scale", ctypes.POINTER(ctypes.c_float))]
 
 
 _vp, _i32, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
@@ -101,13 +102,17 @@ def _shape(B, S, Hq, Hkv, D, dtype, scale):
     return seka_shape(B, S, Hq, Hkv, D, dtype, float(scale))
 
 
-def _steer(U, gain, mask, w, Hkv):
-    """U [Hkv,M,D,r] device tensor; gain: host sequence of Hkv floats; mask [B,S] uint8 device; w [B,Hkv,M] fp32 device or None."""
+def _steer(U, gain, mask, w, Hkv, key_scale=None):
+    """U [Hkv,M,D,r] device tensor; gain: host sequence of Hkv floats; mask [B,S] uint8 device; w [B,Hkv,M] fp32
+    device or None; key_scale: host sequence of Hkv floats or None (all ones)."""
     if U.dim() != 4:
         raise ValueError("U must be [Hkv, M, D, r]")
     gains = (ctypes.c_float * Hkv)(*[float(g) for g in gain])
-    st = seka_steer(int(U.shape[1]), int(U.shape[3]), _dev(U, "U"), _dev(w, "w"), gains, _dev(mask, "mask"))
-    st._keepalive = gains
+    scales = None
+    if key_scale is not None:
+        scales = (ctypes.c_float * Hkv)(*[float(a) for a in key_scale])
+    st = seka_steer(int(U.shape[1]), int(U.shape[3]), _dev(U, "U"), _dev(w, "w"), gains, _dev(mask, "mask"), scales)
+    st._keepalive = (gains, scales)
     return st
 
 
@@ -137,20 +142,20 @@ def seka_route(Q, proto, t0, t1, mode=SEKA_ROUTE_SOFTMAX_COS, tau=10.0, w_out=No
     return w_out
 
 
-def seka_edit_keys(K_in, K_out, U, gain, mask, w=None, stream=None):
+def seka_edit_keys(K_in, K_out, U, gain, mask, w=None, stream=None, key_scale=None):
     """K_in/K_out [B,S,Hkv,D]; K_out may be K_in itself (in place)."""
     B, S, Hkv, D = K_in.shape
     sh = _shape(B, S, Hkv, Hkv, D, _dtype_code(K_in), 0.0)
-    st = _steer(U, gain, mask, w, Hkv)
+    st = _steer(U, gain, mask, w, Hkv, key_scale)
     _check(lib.seka_edit_keys(_dev(K_in, "K_in"), _dev(K_out, "K_out"), ctypes.byref(sh), ctypes.byref(st), _stream(stream)))
     return K_out
 
 
-def seka_attention_prefill(Q, K, V, O, U, gain, mask, w=None, lse=None, scale=0.0, stream=None):
+def seka_attention_prefill(Q, K, V, O, U, gain, mask, w=None, lse=None, scale=0.0, stream=None, key_scale=None):
     B, S, Hq, D = Q.shape
     Hkv = K.shape[2]
     sh = _shape(B, S, Hq, Hkv, D, _dtype_code(Q), scale)
-    st = _steer(U, gain, mask, w, Hkv)
+    st = _steer(U, gain, mask, w, Hkv, key_scale)
     _check(lib.seka_attention_prefill(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(O, "O"), _dev(lse, "lse"),
                                       ctypes.byref(sh), ctypes.byref(st), _stream(stream)))
     return O

@@ -39,8 +39,10 @@ seka_status check_steer(const seka_steer* st, const seka_shape* sh) {
   if ((int64_t)st->M * st->r > SEKA_MAX_RANK) return SEKA_ERR_SHAPE;
   if (st->r > sh->D) return SEKA_ERR_SHAPE;
   if (misaligned(st->U) || (st->w && misaligned(st->w))) return SEKA_ERR_ALIGN;
-  for (int h = 0; h < sh->Hkv; ++h)
+  for (int h = 0; h < sh->Hkv; ++h) {
     if (!std::isfinite(st->gain[h])) return SEKA_ERR_SHAPE;
+    if (st->key_scale && !std::isfinite(st->key_scale[h])) return SEKA_ERR_SHAPE;
+  }
   if (sh->dtype == SEKA_BF16 && st->r % 8 != 0) return SEKA_ERR_UNSUPPORTED;
   return SEKA_OK;
 }
@@ -52,7 +54,10 @@ void fill_steer(seka::SteerArgs& sa, const seka_steer* st, int Hkv) {
   sa.mask = st->mask;
   sa.M = st->M;
   sa.r = st->r;
-  for (int h = 0; h < Hkv; ++h) sa.gain[h] = st->gain[h];
+  for (int h = 0; h < Hkv; ++h) {
+    sa.gain[h] = st->gain[h];
+    sa.kscale[h] = st->key_scale ? st->key_scale[h] : 1.0f;
+  }
 }
 
 bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb) {

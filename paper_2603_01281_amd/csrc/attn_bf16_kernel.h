@@ -95,6 +95,7 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
   const int qi = qw + l32;                       // this lane's query row
 
   const float gain = STEER ? st.gain[h] : 0.f;
+  const float kscale = STEER ? st.kscale[h] : 1.f;
   const bool steer_on = STEER && gain != 0.f;
 
   // ---- Q fragments: B operand of S^T = K Q^T, lane (col = row qi, k = 16 ks + 8 hf + e) ----
@@ -231,7 +232,7 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
             }
           }
 #pragma unroll
-          for (int i = 0; i < 4; ++i) outv[4 * half + i] = (float)kreg[s][4 * half + i] + acc[i];
+          for (int i = 0; i < 4; ++i) outv[4 * half + i] = (float)kreg[s][4 * half + i] * (1.f + mbit * (kscale - 1.f)) + acc[i];
         }
         bf16x8 o;
 #pragma unroll

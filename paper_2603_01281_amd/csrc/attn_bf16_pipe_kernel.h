@@ -127,6 +127,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   const int qi0 = qw + l32;                      // this lane's query row in row block 0 (block rp: + 32 rp)
 
   const float gain = STEER ? st.gain[h] : 0.f;
+  const float kscale = STEER ? st.kscale[h] : 1.f;
   const bool steer_on = STEER && gain != 0.f;
 
   const int last_key = min(S, qb * BQ + BQ) - 1;
@@ -383,6 +384,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 #pragma unroll
     for (int s = 0; s < KS2; ++s) kreg[s] = *reinterpret_cast<const bf16x8*>(krow + 16 * ((4 * s + g) ^ j));
     const float mbit = ((bits16 >> j) & 1u) ? 1.f : 0.f;
+    const float ksc = 1.f + mbit * (kscale - 1.f);        // a for highlighted keys, exactly 1 otherwise
     bf16x8 zb;
     bf16x8 u2[DENSE ? 1 : 2 * KS2];      // low rank: all operands of the second product, requested up front so that
     if (!DENSE) {                        // the product runs back to back instead of one LDS round trip per slice
@@ -422,7 +424,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
         if (!DENSE) {
           const f32x4 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(u2[s * 2 + half], zb, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
 #pragma unroll
-          for (int i = 0; i < 4; ++i) outv[4 * half + i] = (float)kreg[s][4 * half + i] + acc[i];
+          for (int i = 0; i < 4; ++i) outv[4 * half + i] = (float)kreg[s][4 * half + i] * ksc + acc[i];
         } else {
           f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
@@ -432,7 +434,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
           }
 #pragma unroll
           for (int i = 0; i < 4; ++i)
-            outv[4 * half + i] = (float)kreg[s][4 * half + i] + mbit * (acc[0][i] + acc[1][i]);
+            outv[4 * half + i] = (float)kreg[s][4 * half + i] * ksc + mbit * (acc[0][i] + acc[1][i]);
           __builtin_amdgcn_sched_barrier(0);     // keeps the operand reads of later row groups from piling up in registers
         }
       }

@@ -46,6 +46,7 @@ __global__ __launch_bounds__(kThreads) void attention_f32_kernel(AttnArgs a, Ste
   float m_run = -1e30f, l_run = 0.f;
 
   const float gain = STEER ? st.gain[h] : 0.f;
+  const float kscale = STEER ? st.kscale[h] : 1.f;
   const int R = STEER ? st.M * st.r : 0;
   const float* Uh = STEER ? static_cast<const float*>(st.U) + (size_t)h * st.M * D * st.r : nullptr;
 
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(kThreads) void attention_f32_kernel(AttnArgs a, Ste
           const int m = r / st.r, rr = r % st.r;
           acc = fmaf(Uh[((size_t)m * D + d) * st.r + rr], Zs[jj][r], acc);
         }
-        Ks[jj][d] += acc;
+        Ks[jj][d] = fmaf(kscale, Ks[jj][d], acc);
       }
       __syncthreads();
     }

@@ -23,6 +23,7 @@ struct SteerArgs {
   const uint8_t* mask;  // dev [B, S]
   int M, r;
   float gain[SEKA_MAX_KV_HEADS];
+  float kscale[SEKA_MAX_KV_HEADS];   // a of k' = a k + g P k (1 unless Eq. 4's negative-side gain is used)
 };
 
 struct AttnArgs {

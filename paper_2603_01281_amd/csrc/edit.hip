@@ -44,6 +44,7 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint
   const bool valid = t < S;
   const int mk = valid ? st.mask[(size_t)b * S + t] : 0;
   const float gain = st.gain[h];
+  const float kscale = st.kscale[h];
   const bool wave_hl = __ballot(mk != 0) != 0ull;
   const bool block_hl = __syncthreads_or(mk != 0) != 0;
   const bool steered = block_hl && gain != 0.f;
@@ -152,7 +153,7 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint
         }
       }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) outv[4 * half + i] = (float)kreg[s][4 * half + i] + acc[i];
+      for (int i = 0; i < 4; ++i) outv[4 * half + i] = (float)kreg[s][4 * half + i] * (1.f + mbit * (kscale - 1.f)) + acc[i];
     }
     bf16x8 o;
 #pragma unroll
@@ -174,6 +175,7 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_f32_kernel(const float
   const int b = blockIdx.z, h = blockIdx.y;
   const int t0 = blockIdx.x * TT;
   const float gain = st.gain[h];
+  const float kscale = st.kscale[h];
   const int R = st.M * st.r;
   int any = 0;
   if (threadIdx.x < TT) {
@@ -214,7 +216,7 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_f32_kernel(const float
         const int m = r / st.r, rr = r % st.r;
         acc = fmaf(Uh[((size_t)m * D + d) * st.r + rr], z[tt][r], acc);
       }
-      v += acc;
+      v = fmaf(kscale, v, acc);
     }
     if (!inplace || edited) K_out[(((size_t)b * S + t) * Hkv + h) * D + d] = v;
   }

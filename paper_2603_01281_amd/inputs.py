@@ -38,7 +38,7 @@ def _rng(seed, stream):
 
 
 # stream ids, one per tensor kind (layer index is added in the upper bits)
-_STREAM = {"Q": 1, "K": 2, "V": 3, "U": 4, "mask": 5, "proto": 6, "gain": 7, "sigma": 8}
+_STREAM = {"Q": 1, "K": 2, "V": 3, "U": 4, "mask": 5, "proto": 6, "gain": 7, "sigma": 8, "svd": 9}
 
 
 def _stream(kind, layer=0):
@@ -104,6 +104,23 @@ def orthonormal_bases(Hkv, M, D, r, seed, dtype, layer=0):
             Qf, Rf = np.linalg.qr(A)
             U[h, m] = Qf * np.sign(np.diag(Rf))[None, :]
     return _store(U.astype(np.float32), dtype)
+
+
+def singular_vector_sets(Hkv, D, seed, layer=0):
+    """Stand-ins for the left singular vectors of the two cross-covariance matrices of one layer
+    (paper Sec. 3.1): two independent D x D orthogonal matrices per KV head, float64."""
+    g = _rng(seed, _stream("svd", layer))
+    out = np.empty((2, Hkv, D, D), dtype=np.float64)
+    for s in range(2):
+        for h in range(Hkv):
+            Qf, Rf = np.linalg.qr(g.standard_normal(size=(D, D)))
+            out[s, h] = Qf * np.sign(np.diag(Rf))[None, :]
+    return out[0], out[1]
+
+
+def store(x, dtype):
+    """float array -> storage form of `dtype` ("f32": float32, "bf16": uint16 bit patterns, round to nearest even)."""
+    return _store(np.asarray(x, dtype=np.float32), dtype)
 
 
 def unit_prototypes(Hkv, M, D, seed, layer=0):

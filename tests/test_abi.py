@@ -45,10 +45,10 @@ def _shape(B, **kw):
 
 def _steer(B, Hkv=2, **kw):
     gains = (ctypes.c_float * Hkv)(*([1.0] * Hkv))
-    d = dict(M=1, r=8, U=FAKE, w=None, gain=gains, mask=FAKE)
+    d = dict(M=1, r=8, U=FAKE, w=None, gain=gains, mask=FAKE, key_scale=None)
     d.update(kw)
-    st = B.seka_steer(d["M"], d["r"], d["U"], d["w"], d["gain"], d["mask"])
-    st._keep = gains
+    st = B.seka_steer(d["M"], d["r"], d["U"], d["w"], d["gain"], d["mask"], d["key_scale"])
+    st._keep = (gains, d["key_scale"])
     return st
 
 
@@ -78,6 +78,7 @@ def test_steering_rejects_bad_arguments(B):
     assert call(_steer(B, M=0)) == 2
     assert call(_steer(B, M=4, r=64)) == 2          # M*r > 128
     assert call(_steer(B, r=80)) == 2               # r > D
+    assert call(_steer(B, key_scale=(ctypes.c_float * 2)(1.0, float("inf")))) == 2     # key scale must be finite
     assert call(_steer(B, U=FAKE + 2)) == 4
     bad_gain = (ctypes.c_float * 2)(1.0, float("nan"))
     assert call(_steer(B, gain=bad_gain)) == 2

@@ -125,8 +125,11 @@ def time_config(torch, seka, inputs, cfg, iters=10):
         w = seka.seka_route(Q, proto, 0, S, seka.SEKA_ROUTE_SOFTMAX_COS, 10.0)
         ws = torch.empty(seka.seka_route_workspace_bytes(B, S, Hq, Hkv, D, seka.SEKA_BF16, 0, S), dtype=torch.uint8, device="cuda")
         route_ms = event_time(torch, lambda: seka.seka_route(Q, proto, 0, S, seka.SEKA_ROUTE_SOFTMAX_COS, 10.0, w_out=w, workspace=ws), iters)
-    plain = event_time(torch, lambda: seka.seka_attention_plain(Q, K, V, O), iters)
-    steer = event_time(torch, lambda: seka.seka_attention_prefill(Q, K, V, O, U, gain, mask, w=w), iters)
+    # The GPU's clock depends on recent load: warm up with both kernels for >= 100 ms, then take per-launch
+    # medians of interleaved launches so that both see the same clock state.
+    run_plain = lambda: seka.seka_attention_plain(Q, K, V, O)
+    run_steer = lambda: seka.seka_attention_prefill(Q, K, V, O, U, gain, mask, w=w)
+    plain, steer = paired_medians(torch, run_plain, run_steer, attn_flops(B, S, Hq, D))
     fl = attn_flops(B, S, Hq, D)
     out = {"plain_ms": round(plain, 4), "steered_ms": round(steer, 4), "steered_tflops": round(fl / steer / 1e9, 1),
            "overhead_pct": round(100 * (steer / plain - 1), 2), "tokens_per_s": round(B * S / steer * 1e3)}
@@ -139,6 +142,24 @@ def time_config(torch, seka, inputs, cfg, iters=10):
     out["edit_keys_ms"] = round(edit_ms, 4)
     out["edit_keys_GBps"] = round(2 * K.numel() * 2 / edit_ms / 1e6, 1)
     return out
+
+
+def paired_medians(torch, fn_a, fn_b, flops, n=15):
+    for _ in range(max(10, int(120.0 / (flops / 1.0e12)))):      # ~1 PFLOP/s => ms per launch ~ flops / 1e12
+        fn_a()
+        fn_b()
+    torch.cuda.synchronize()
+    ev = {0: [], 1: []}
+    for _ in range(n):
+        for k, fn in ((0, fn_a), (1, fn_b)):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            fn()
+            e1.record()
+            ev[k].append((e0, e1))
+    torch.cuda.synchronize()
+    med = lambda xs: sorted(a.elapsed_time(b) for a, b in xs)[len(xs) // 2]
+    return med(ev[0]), med(ev[1])
 
 
 def event_time(torch, fn, iters, warm=3):

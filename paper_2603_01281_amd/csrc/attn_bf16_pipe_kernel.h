@@ -88,8 +88,8 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 
 #ifdef SEKA_CYCLE_PROBE
   // Diagnostic build: per-wave shader-clock counters, written over the LSE rows of the wave's first queries.
-  const unsigned long long prb_entry = __builtin_amdgcn_s_memtime();
-  unsigned long long prb_edit = 0ull, prb_n = 0ull, prb_wait = 0ull, prb_bar = 0ull;
+  unsigned long long prb_entry = __builtin_amdgcn_s_memtime();
+  unsigned long long prb_edit = 0ull, prb_n = 0ull, prb_wait = 0ull, prb_bar = 0ull, prb_issued = 0ull;
 #endif
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   unsigned char* Kst = smem;                                     // [3][16 KB] swizzled K tiles
@@ -112,26 +112,32 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   const int G = a.Hq / a.Hkv;
   const int nHC = a.Hq / HPW;
   const int nQB = (S + BQ - 1) / BQ;
+  // A workgroup handles two blocks of query rows of one (batch, head group), one after the other: block
+  // nQB - 1 - p and block p.  Every workgroup then scans nQB + 1 key tiles (no imbalance from causality), the
+  // steering set-up is done once for both, and the first loads of the second block overlap the first block's
+  // output stores.  (With nQB odd the middle block is on its own.)
   const int per_qb = nHC * a.B;
-  const int qb = nQB - 1 - (int)(blockIdx.x / per_qb);
+  const int pair = (int)(blockIdx.x / per_qb);
   const int rem = blockIdx.x % per_qb;
   const int b = rem / nHC, hc = rem % nHC;
   const int hq0 = hc * HPW;
   const int h = hq0 / G;
+  const int npass = (nQB - 1 - pair != pair) ? 2 : 1;
+  int qb = nQB - 1 - pair;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, hf = lane >> 5;
   const int hq = hq0 + wave / RBW;
-  const int qw = qb * BQ + WR * (wave % RBW);    // first query row of this wave
-  const int qi0 = qw + l32;                      // this lane's query row in row block 0 (block rp: + 32 rp)
+  int qw = qb * BQ + WR * (wave % RBW);    // first query row of this wave
+  int qi0 = qw + l32;                      // this lane's query row in row block 0 (block rp: + 32 rp)
 
   const float gain = STEER ? st.gain[h] : 0.f;
   const float kscale = STEER ? st.kscale[h] : 1.f;
   const bool steer_on = STEER && gain != 0.f;
 
-  const int last_key = min(S, qb * BQ + BQ) - 1;
-  const int ntiles = last_key / BK + 1;
+  int last_key = min(S, qb * BQ + BQ) - 1;
+  int ntiles = last_key / BK + 1;          // the first block is the later one: its tile count bounds the second's
 
   // ---- tile loads: scalar tile base + per-lane offset fixed for the whole kernel ----
   // Slot s of a tile is LDS bytes [1024 s, 1024 s + 1024) = rows 4s..4s+3; lane l lands at row 4s + l/16,
@@ -175,21 +181,24 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     issue_rows(std::false_type{}, Vbytes, t, vst_base + (t % 3) * TB, voff);
   };
 
-  issue_k(0);
-  issue_v(0);
-  if (ntiles > 1) { issue_k(1); issue_v(1); }
-
   // ---- Q fragments: B operand of S^T = K Q^T, lane (col = row qi, k = 16 ks + 8 hf + e) ----
   bf16x8 qf[RPW][KS];
+  // First loads of a block of query rows: K/V tiles 0 and 1, then the wave's Q rows.
+  auto begin_block = [&]() __attribute__((always_inline)) {
+    issue_k(0);
+    issue_v(0);
+    if (ntiles > 1) { issue_k(1); issue_v(1); }
 #pragma unroll
-  for (int rp = 0; rp < RPW; ++rp) {
-    const int qi = qi0 + 32 * rp;
-    const bool ok = qi < S;
-    const uint16_t* qp = Qg + (((size_t)b * S + (ok ? qi : 0)) * a.Hq + hq) * D + 8 * hf;
+    for (int rp = 0; rp < RPW; ++rp) {
+      const int qi = qi0 + 32 * rp;
+      const bool ok = qi < S;
+      const uint16_t* qp = Qg + (((size_t)b * S + (ok ? qi : 0)) * a.Hq + hq) * D + 8 * hf;
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks)     // rows past the end read row 0 (finite data, results never stored):
-      qf[rp][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + 16 * ks));   // no branch, no wait here
-  }
+      for (int ks = 0; ks < KS; ++ks)     // rows past the end read row 0 (finite data, results never stored):
+        qf[rp][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + 16 * ks));   // no branch, no wait here
+    }
+  };
+  begin_block();
 
   // ---- steering set-up: edit operands, per-column coefficients, highlight bitmap ----
   // Every global load of the set-up (mask bytes, U_cat, routing weights) is issued before the first of them is
@@ -445,6 +454,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     }
   };
 
+  for (int pass = 0;; ++pass) {      // one turn per block of query rows (indentation of the body kept flat)
   // ---- math pieces ----
   f32x16 oacc[RPW][DB];
 #pragma unroll
@@ -569,7 +579,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   const int tw_last = wave_rows_exist ? min(ntiles - 1, (qw + WR - 1) / BK) : -1;   // last tile this wave computes on
 
 #ifdef SEKA_CYCLE_PROBE
-  const unsigned long long prb_issued = __builtin_amdgcn_s_memtime();
+  if (pass == 0) prb_issued = __builtin_amdgcn_s_memtime();
 #endif
   // ---- prologue: wait for the first tiles, edit K(0) and K(1), first block of S^T ----
   dma_wait_vmcnt<0>();   // also covers the Q, U and mask loads issued after the tile loads
@@ -776,10 +786,40 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     bottom(std::false_type{}, t);
   }
 
-  // ---- epilogue ----
+#ifdef SEKA_CYCLE_PROBE
+  if (a.lse && lane == 0 && qi0 < S) {
+    float* dp = a.lse + ((size_t)b * a.Hq + hq) * S + qi0;
+    dp[0] = (float)(prb_start - prb_entry);                          // set-up until the first tiles are usable
+    dp[1] = (float)(__builtin_amdgcn_s_memtime() - prb_start);       // loops of this block
+    dp[2] = (float)(__builtin_amdgcn_s_memrealtime() - prb_rstart);  // the same span in 100 MHz ticks
+    dp[3] = (float)prb_wait;                                         // waiting for tile loads
+    dp[4] = (float)prb_bar;                                          // waiting at the per-tile barrier
+    dp[5] = (float)prb_edit;                                         // key edits incl. their barrier
+    dp[6] = (float)prb_n;
+    dp[7] = (float)(prb_tail - prb_start);                           // prologue edits and pipelined iterations
+    dp[8] = (float)(prb_issued - prb_entry);                         // set-up until every load has been issued
+  }
+  prb_edit = prb_n = prb_wait = prb_bar = 0ull;
+  prb_entry = __builtin_amdgcn_s_memtime();
+#endif
+  // ---- next block's first loads (every wave is past the last barrier: the tile rings are free), then this
+  // block's output ----
+  const int qi_out = qi0;
+  const bool more = pass + 1 < npass;
+  if (more) {
+    qb = pair;
+    qw = qb * BQ + WR * (wave % RBW);
+    qi0 = qw + l32;
+    last_key = min(S, qb * BQ + BQ) - 1;
+    ntiles = last_key / BK + 1;
+    begin_block();
+  }
+#ifdef SEKA_CYCLE_PROBE
+  prb_issued = __builtin_amdgcn_s_memtime();
+#endif
 #pragma unroll
   for (int rp = 0; rp < RPW; ++rp) {
-    const int qi = qi0 + 32 * rp;
+    const int qi = qi_out + 32 * rp;
     const float l_tot = l_run[rp] + __shfl_xor(l_run[rp], 32);
     if (qi < S) {
       const float inv = 1.f / l_tot;
@@ -794,25 +834,14 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
           *reinterpret_cast<uint2*>(op + 32 * db + 8 * q4) = __builtin_bit_cast(uint2, o4);
         }
       }
-#ifdef SEKA_CYCLE_PROBE
-      if (a.lse && lane == 0 && rp == 0) {
-        float* dp = a.lse + ((size_t)b * a.Hq + hq) * S + qi;
-        dp[0] = (float)(prb_start - prb_entry);                          // set-up until the first tiles are usable
-        dp[1] = (float)(__builtin_amdgcn_s_memtime() - prb_start);       // loop and epilogue
-        dp[2] = (float)(__builtin_amdgcn_s_memrealtime() - prb_rstart);  // the same span in 100 MHz ticks
-        dp[3] = (float)prb_wait;                                         // waiting for tile loads
-        dp[4] = (float)prb_bar;                                          // waiting at the per-tile barrier
-        dp[5] = (float)prb_edit;                                         // key edits incl. their barrier
-        dp[6] = (float)prb_n;
-        dp[8] = (float)(prb_issued - prb_entry);                         // set-up until every load has been issued
-        dp[7] = (float)(prb_tail - prb_start);                           // prologue edits and pipelined iterations
-      }
-      if (false)
-#endif
+#ifndef SEKA_CYCLE_PROBE
       // m_run is the reference exponent in units of s * scale * log2(e); l_tot is relative to it
       if (a.lse && hf == 0) a.lse[((size_t)b * a.Hq + hq) * S + qi] = m_run[rp] * 0.6931471805599453f + logf(l_tot);
+#endif
     }
   }
+  if (!more) break;
+  }   // for pass
 }
 
 }  // namespace seka

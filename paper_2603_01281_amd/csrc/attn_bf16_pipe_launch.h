@@ -17,7 +17,7 @@ hipError_t launch_attention_bf16_pipe_cfg(const AttnArgs& a, const SteerArgs* st
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (e != hipSuccess) return e;
   const int nQB = (a.S + BQ - 1) / BQ;
-  const long long blocks = (long long)nQB * (a.Hq / HPW) * a.B;
+  const long long blocks = (long long)((nQB + 1) / 2) * (a.Hq / HPW) * a.B;     // two blocks of query rows per workgroup
   if (blocks > 0x7fffffffLL) return hipErrorNotSupported;
   SteerArgs sa;
   if (STEER) sa = *steer; else memset(&sa, 0, sizeof(sa));

@@ -21,6 +21,8 @@ What is written out here, in the order the paper states it:
                                                                      signed low-rank update, fed to edit_keys)
 * Sec. 2           Attn(i, j) = q_i . k_j / sqrt(d_k), causal softmax, weighted sum of V
                                                                   -> causal_attention
+* generation step  the same attention for one new query per prompt over a cache of (edited) keys
+                                                                  -> decode_attention
 * Eq. 6            alpha_m = sum_k (q.u_m^(k)) sigma_m^(k) / max_m |.|   -> route_eq6
 * benchmark's routing rule  w = softmax_m(tau * cos(mean prompt query, prototype_m))
                                                                   -> route_softmax_cos
@@ -198,6 +200,36 @@ def attention_rows(Q, K, V, rows, scale=None):
         out[n] = (e / s) @ v
         lse[n] = a_max + np.log(s)
     return out, lse
+
+
+def decode_attention(q, K, V, lens=None, scale=None):
+    """Generation step after the prompt (the edited keys persist in the KV cache, Algorithm 1's hook ran at
+    prefill): one new query per (prompt, head) attends to the first lens[b] cached keys, its own included.
+
+    q[B,Hq,d]; K, V [B,Tmax,H,d] caches (K already edited where the prompt was highlighted);
+    lens[B] number of valid cached tokens per prompt, or None for Tmax.
+    Returns O[B,Hq,d] and LSE[B,Hq].
+    """
+    q = np.asarray(q, dtype=_F)
+    B, Hq, d = q.shape
+    H = K.shape[2]
+    G = Hq // H
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    O = np.empty((B, Hq, d), dtype=_F)
+    LSE = np.empty((B, Hq), dtype=_F)
+    for b in range(B):
+        n = K.shape[1] if lens is None else int(lens[b])
+        for hq in range(Hq):
+            h = hq // G
+            k = np.asarray(K[b, :n, h, :], dtype=_F)
+            v = np.asarray(V[b, :n, h, :], dtype=_F)
+            a = scale * (k @ q[b, hq])
+            a_max = a.max()
+            e = np.exp(a - a_max)
+            O[b, hq] = (e / e.sum()) @ v
+            LSE[b, hq] = a_max + np.log(e.sum())
+    return O, LSE
 
 
 def mean_group_query(Q, H, t0, t1):

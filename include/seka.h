@@ -129,6 +129,25 @@ seka_status seka_attention_prefill(const void* Q, const void* K, const void* V, 
 seka_status seka_attention_plain(const void* Q, const void* K, const void* V, void* O, float* lse,
                                  const seka_shape* sh, void* hip_stream);
 
+/*
+ * seka_attention_decode — the generation step after a steered prefill.  The edited keys persist in the KV
+ * cache (run seka_edit_keys in place on the prompt's keys, the hook of Algorithm 1), so the new token's query
+ * attends to the cache as it is: logits q . k_j / sqrt(d_k) over the first seq_lens[b] cached tokens (its own
+ * key included), softmax, O = sum_j p_j v_j (paper Sec. 2).  Memory-bound: K and V are read once.
+ *
+ * q, O      dev [B,Hq,D] tensor dtype (one query per prompt and head).
+ * K, V      dev [B,S,Hkv,D] tensor dtype: the caches; sh->S is their capacity in tokens.
+ * lse       dev [B,Hq] fp32 or NULL.
+ * seq_lens  dev [B] int32 or NULL (= S for every prompt); values are clamped to [0, S]; a prompt with no
+ *           cached token gets O = 0 and lse = -inf.
+ * workspace dev scratch of at least seka_decode_workspace_bytes(sh) bytes, 16-byte aligned; contents on return
+ *           are unspecified; calls sharing it must be ordered by their stream.
+ */
+size_t seka_decode_workspace_bytes(const seka_shape* sh);
+seka_status seka_attention_decode(const void* q, const void* K, const void* V, void* O, float* lse,
+                                  const int32_t* seq_lens, const seka_shape* sh, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream);
+
 /* Name of a status code; static storage, never NULL. */
 const char* seka_status_string(int32_t status);
 

@@ -55,6 +55,10 @@ lib.seka_edit_keys.restype = _i32
 lib.seka_edit_keys.argtypes = [_vp, _vp, _shape_p, _steer_p, _vp]
 lib.seka_attention_prefill.restype = _i32
 lib.seka_attention_prefill.argtypes = [_vp, _vp, _vp, _vp, _vp, _shape_p, _steer_p, _vp]
+lib.seka_decode_workspace_bytes.restype = _sz
+lib.seka_decode_workspace_bytes.argtypes = [_shape_p]
+lib.seka_attention_decode.restype = _i32
+lib.seka_attention_decode.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _shape_p, _vp, _sz, _vp]
 lib.seka_attention_plain.restype = _i32
 lib.seka_attention_plain.argtypes = [_vp, _vp, _vp, _vp, _vp, _shape_p, _vp]
 
@@ -167,4 +171,24 @@ def seka_attention_plain(Q, K, V, O, lse=None, scale=0.0, stream=None):
     sh = _shape(B, S, Hq, Hkv, D, _dtype_code(Q), scale)
     _check(lib.seka_attention_plain(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(O, "O"), _dev(lse, "lse"),
                                     ctypes.byref(sh), _stream(stream)))
+    return O
+
+
+def seka_decode_workspace_bytes(B, S, Hq, Hkv, D, dtype):
+    sh = _shape(B, S, Hq, Hkv, D, dtype, 0.0)
+    return lib.seka_decode_workspace_bytes(ctypes.byref(sh))
+
+
+def seka_attention_decode(q, K, V, O, seq_lens=None, lse=None, scale=0.0, workspace=None, stream=None):
+    """q/O [B,Hq,D]; K/V [B,S,Hkv,D] caches; seq_lens [B] int32 device tensor or None."""
+    torch = _torch()
+    B, Hq, D = q.shape
+    S, Hkv = K.shape[1], K.shape[2]
+    sh = _shape(B, S, Hq, Hkv, D, _dtype_code(q), scale)
+    need = lib.seka_decode_workspace_bytes(ctypes.byref(sh))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=q.device)
+    _check(lib.seka_attention_decode(_dev(q, "q"), _dev(K, "K"), _dev(V, "V"), _dev(O, "O"), _dev(lse, "lse"),
+                                     _dev(seq_lens, "seq_lens"), ctypes.byref(sh), _dev(workspace, "workspace"),
+                                     workspace.numel() * workspace.element_size(), _stream(stream)))
     return O

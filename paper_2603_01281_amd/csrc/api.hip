@@ -171,6 +171,34 @@ seka_status seka_edit_keys(const void* K_in, void* K_out, const seka_shape* sh, 
   return launch_status(e);
 }
 
+size_t seka_decode_workspace_bytes(const seka_shape* sh) {
+  if (check_shape(sh, true) != SEKA_OK) return 0;
+  return seka::decode_workspace_bytes(sh->B, sh->S, sh->Hq, sh->Hkv, sh->D);
+}
+
+seka_status seka_attention_decode(const void* q, const void* K, const void* V, void* O, float* lse,
+                                  const int32_t* seq_lens, const seka_shape* sh, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream) {
+  seka_status rc = check_shape(sh, true);
+  if (rc != SEKA_OK) return rc;
+  if (!q || !K || !V || !O) return SEKA_ERR_NULL;
+  if (misaligned(q) || misaligned(K) || misaligned(V) || misaligned(O)) return SEKA_ERR_ALIGN;
+  if ((lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) || (seq_lens && (reinterpret_cast<uintptr_t>(seq_lens) & 3u)))
+    return SEKA_ERR_ALIGN;
+  const size_t es = elem_size(sh->dtype);
+  const size_t nq = (size_t)sh->B * sh->Hq * sh->D * es;
+  const size_t nk = (size_t)sh->B * sh->S * sh->Hkv * sh->D * es;
+  if (ranges_overlap(O, nq, q, nq) || ranges_overlap(O, nq, K, nk) || ranges_overlap(O, nq, V, nk)) return SEKA_ERR_ALIAS;
+  const size_t need = seka::decode_workspace_bytes(sh->B, sh->S, sh->Hq, sh->Hkv, sh->D);
+  if (!workspace || workspace_bytes < need) return SEKA_ERR_WORKSPACE;
+  if (misaligned(workspace)) return SEKA_ERR_ALIGN;
+  const float scale = sh->softmax_scale > 0.0f ? sh->softmax_scale : 1.0f / std::sqrt((float)sh->D);
+  (void)hipGetLastError();
+  hipError_t e = seka::launch_decode(q, K, V, O, lse, seq_lens, sh->B, sh->S, sh->Hq, sh->Hkv, sh->D, sh->dtype, scale,
+                                     workspace, reinterpret_cast<hipStream_t>(hip_stream));
+  return launch_status(e);
+}
+
 seka_status seka_attention_prefill(const void* Q, const void* K, const void* V, void* O, float* lse,
                                    const seka_shape* sh, const seka_steer* st, void* hip_stream) {
   return attention_common(Q, K, V, O, lse, sh, st, hip_stream);

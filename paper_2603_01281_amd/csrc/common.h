@@ -47,6 +47,10 @@ hipError_t launch_route(const void* Q, int B, int S, int Hq, int Hkv, int D, int
                         int M, int t0, int t1, int mode, float tau, float* w_out, void* workspace,
                         hipStream_t s);
 
+size_t decode_workspace_bytes(int B, int S, int Hq, int Hkv, int D);
+hipError_t launch_decode(const void* q, const void* K, const void* V, void* O, float* lse, const int* lens, int B, int S,
+                         int Hq, int Hkv, int D, int dtype, float scale, void* workspace, hipStream_t s);
+
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
 }  // namespace seka

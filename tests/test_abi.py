@@ -20,7 +20,8 @@ def test_exports_every_declared_symbol(B):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(seka_[a-z_0-9]+)\s*\(", header))
     assert {"seka_route", "seka_edit_keys", "seka_attention_prefill", "seka_attention_plain",
-            "seka_route_workspace_bytes", "seka_status_string", "seka_set_tuning"} <= names
+            "seka_route_workspace_bytes", "seka_status_string", "seka_set_tuning",
+            "seka_attention_decode", "seka_decode_workspace_bytes"} <= names
     for n in names:
         assert hasattr(B.lib, n), f"libseka.so does not export {n}"
 
@@ -113,3 +114,20 @@ def test_tuning_rejects_unknown(B):
     assert B.lib.seka_set_tuning(99, 0) == 6
     assert B.lib.seka_set_tuning(0, 12345) == 6
     assert B.lib.seka_set_tuning(0, 0) == 0
+
+
+def test_decode_rejects_bad_arguments(B):
+    L = B.lib
+    ok = _shape(B)
+    need = L.seka_decode_workspace_bytes(ctypes.byref(ok))
+    assert need > 0 and need % 4 == 0
+    far, ws = FAKE * 64, FAKE * 128
+    call = lambda q, o, sh=ok, w=ws, wb=need, lens=None: L.seka_attention_decode(q, FAKE * 4, FAKE * 8, o, None, lens, ctypes.byref(sh), w, wb, None)
+    assert call(None, far) == 1
+    assert call(FAKE, far, _shape(B, D=96)) == 2
+    assert call(FAKE + 2, far) == 4
+    assert call(FAKE, far, lens=FAKE + 2) == 4
+    assert call(FAKE, FAKE) == 5                      # O aliases q
+    assert call(FAKE, far, w=None) == 8
+    assert call(FAKE, far, wb=need - 1) == 8
+    assert L.seka_decode_workspace_bytes(ctypes.byref(_shape(B, Hq=5))) == 0

@@ -141,6 +141,13 @@ def time_config(torch, seka, inputs, cfg, iters=10):
     edit_ms = event_time(torch, lambda: seka.seka_edit_keys(K, K2, U, gain, mask, w=w), iters, warm=10)
     out["edit_keys_ms"] = round(edit_ms, 4)
     out["edit_keys_GBps"] = round(2 * K.numel() * 2 / edit_ms / 1e6, 1)
+    # generation step over the (edited) cache: reads K and V once
+    qd = Q[:, -1].contiguous()
+    Od = torch.empty_like(qd)
+    wsd = torch.empty(seka.seka_decode_workspace_bytes(B, S, Hq, Hkv, D, seka.SEKA_BF16), dtype=torch.uint8, device="cuda")
+    dec_ms = event_time(torch, lambda: seka.seka_attention_decode(qd, K2, V, Od, workspace=wsd), iters, warm=10)
+    out["decode_ms"] = round(dec_ms, 4)
+    out["decode_GBps"] = round(2 * K.numel() * 2 / dec_ms / 1e6, 1)
     return out
 
 

@@ -20,6 +20,8 @@ constexpr int kDecThreads = 256;
 constexpr int kDecWaves = kDecThreads / 64;
 constexpr float kDecSlack = 8.f;        // a head's reference exponent trails its maximum by at most this
 constexpr float kNegBig = -1e30f;
+// split policy (measured on MI355X: more, smaller splits lose to the merge stage; fewer leave CUs idle)
+constexpr int kDecTargetWG = 4096, kDecMinRows = 512, kDecMaxSplits = 64;
 
 __host__ __device__ inline int decode_heads_per_group(int G) {
   if (G <= 8) return G;
@@ -28,12 +30,13 @@ __host__ __device__ inline int decode_heads_per_group(int G) {
   return 1;
 }
 
+// Splits of the cached range per (prompt, head group): about kDecTargetWG workgroups in all, at least kDecMinRows tokens each.
 __host__ __device__ inline int decode_splits(int B, int Hkv, int G, int S) {
   const int groups = B * Hkv * (G / decode_heads_per_group(G));
-  int want = (1024 + groups - 1) / groups;
-  const int cap = S / 256 > 1 ? S / 256 : 1;
+  int want = (kDecTargetWG + groups - 1) / groups;
+  const int cap = S / kDecMinRows > 1 ? S / kDecMinRows : 1;
   if (want > cap) want = cap;
-  if (want > 64) want = 64;
+  if (want > kDecMaxSplits) want = kDecMaxSplits;
   return want < 1 ? 1 : want;
 }
 
@@ -54,6 +57,10 @@ template <> struct DecElem<uint16_t> {
     *p = __builtin_bit_cast(uint16_t, b);
   }
 };
+__device__ __forceinline__ float dec_dot2(uint32_t a, uint32_t b, float c) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a), __builtin_bit_cast(bf16x2, b), c, false);
+}
+
 template <> struct DecElem<float> {
   static constexpr int EPL = 4;
   __device__ static void load(const float* p, float (&out)[4]) {
@@ -128,38 +135,110 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(const T* __
   const T* Kb = K + ((size_t)b * S * Hkv + h) * D + c * EPL;
   const T* Vb = V + ((size_t)b * S * Hkv + h) * D + c * EPL;
   const int step = kDecWaves * KPW;                      // rows per workgroup turn
+  constexpr bool PACKED = sizeof(T) == 2;      // bf16: both products on the packed dot-product instruction
+  uint32_t qw[GP][4];                          // PACKED: the query chunk as it is stored (pairs of bf16)
+  if (PACKED) {
+#pragma unroll
+    for (int g = 0; g < GP; ++g) {
+      const uint4 t4 = *reinterpret_cast<const uint4*>(q + ((size_t)b * Hq + hq0 + g) * D + c * EPL);
+      qw[g][0] = t4.x; qw[g][1] = t4.y; qw[g][2] = t4.z; qw[g][3] = t4.w;
+    }
+  }
   for (int turn = k0; turn < k1; turn += UNR * step) {      // workgroup-uniform trip count
     const int base = turn + wave * KPW + kk;
-    float kf[UNR][EPL], vf[UNR][EPL];
     bool ok[UNR];
+    float sc[UNR][GP];
+    if (PACKED) {
+      uint4 kr[UNR], vr[UNR];
 #pragma unroll
-    for (int u = 0; u < UNR; ++u) {
-      const int row = base + u * step;
-      ok[u] = row < k1;
-      const size_t r = (size_t)(ok[u] ? row : k1 - 1) * rowstride;      // clamped: loads stay inside the cache
-      DecElem<T>::load(Kb + r, kf[u]);
-      DecElem<T>::load(Vb + r, vf[u]);
-    }
+      for (int u = 0; u < UNR; ++u) {
+        const int row = base + u * step;
+        ok[u] = row < k1;
+        const size_t r = (size_t)(ok[u] ? row : k1 - 1) * rowstride;      // clamped: loads stay inside the cache
+        kr[u] = *reinterpret_cast<const uint4*>(Kb + r);
+        vr[u] = *reinterpret_cast<const uint4*>(Vb + r);
+      }
 #pragma unroll
-    for (int u = 0; u < UNR; ++u) {
+      for (int u = 0; u < UNR; ++u) {
+#pragma unroll
+        for (int g = 0; g < GP; ++g) {
+          float t = dec_dot2(qw[g][0], kr[u].x, 0.f);
+          t = dec_dot2(qw[g][1], kr[u].y, t);
+          t = dec_dot2(qw[g][2], kr[u].z, t);
+          t = dec_dot2(qw[g][3], kr[u].w, t);
+          t = row_sum<LPR>(t) * c2;
+          sc[u][g] = ok[u] ? t : -INFINITY;
+        }
+      }
+      // one reference check per head and turn; probabilities are rounded to bf16 and that rounded value feeds both
+      // the row sum and the PV product (two cached rows per packed instruction)
+      uint32_t pp[UNR / 2][GP];
 #pragma unroll
       for (int g = 0; g < GP; ++g) {
-        float s = 0.f;
+        float smax = sc[0][g];
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) s = fmaf(qv[g][e], kf[u][e], s);
-        s = row_sum<LPR>(s) * c2;
-        if (!ok[u]) s = -INFINITY;
-        if (s > m[g] + kDecSlack) {                      // raise the reference exponent (rare after the first rows)
-          const float alpha = __builtin_amdgcn_exp2f(m[g] - s);
-          m[g] = s;
+        for (int u = 1; u < UNR; ++u) smax = fmaxf(smax, sc[u][g]);
+        if (smax > m[g] + kDecSlack) {                     // rare after the first rows
+          const float alpha = __builtin_amdgcn_exp2f(m[g] - smax);
+          m[g] = smax;
           l[g] *= alpha;
 #pragma unroll
           for (int e = 0; e < EPL; ++e) o[g][e] *= alpha;
         }
-        const float p = __builtin_amdgcn_exp2f(s - m[g]);
-        l[g] += p;
 #pragma unroll
-        for (int e = 0; e < EPL; ++e) o[g][e] = fmaf(p, vf[u][e], o[g][e]);
+        for (int pr = 0; pr < UNR / 2; ++pr) {
+          const bf16x2 p2 = {(__bf16)__builtin_amdgcn_exp2f(sc[2 * pr][g] - m[g]),
+                             (__bf16)__builtin_amdgcn_exp2f(sc[2 * pr + 1][g] - m[g])};
+          pp[pr][g] = __builtin_bit_cast(uint32_t, p2);
+          l[g] = dec_dot2(pp[pr][g], 0x3f803f80u, l[g]);
+        }
+      }
+#pragma unroll
+      for (int pr = 0; pr < UNR / 2; ++pr) {
+        const uint32_t va[4] = {vr[2 * pr].x, vr[2 * pr].y, vr[2 * pr].z, vr[2 * pr].w};
+        const uint32_t vb[4] = {vr[2 * pr + 1].x, vr[2 * pr + 1].y, vr[2 * pr + 1].z, vr[2 * pr + 1].w};
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const uint32_t lo = __builtin_amdgcn_perm(vb[w], va[w], 0x05040100u);   // (row a, row b) of element 2 w
+          const uint32_t hi = __builtin_amdgcn_perm(vb[w], va[w], 0x07060302u);   // ... of element 2 w + 1
+#pragma unroll
+          for (int g = 0; g < GP; ++g) {
+            o[g][2 * w] = dec_dot2(lo, pp[pr][g], o[g][2 * w]);
+            o[g][2 * w + 1] = dec_dot2(hi, pp[pr][g], o[g][2 * w + 1]);
+          }
+        }
+      }
+    } else {
+      float kf[UNR][EPL], vf[UNR][EPL];
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        const int row = base + u * step;
+        ok[u] = row < k1;
+        const size_t r = (size_t)(ok[u] ? row : k1 - 1) * rowstride;
+        DecElem<T>::load(Kb + r, kf[u]);
+        DecElem<T>::load(Vb + r, vf[u]);
+      }
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+#pragma unroll
+        for (int g = 0; g < GP; ++g) {
+          float s = 0.f;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) s = fmaf(qv[g][e], kf[u][e], s);
+          s = row_sum<LPR>(s) * c2;
+          if (!ok[u]) s = -INFINITY;
+          if (s > m[g] + kDecSlack) {                      // raise the reference exponent (rare after the first rows)
+            const float alpha = __builtin_amdgcn_exp2f(m[g] - s);
+            m[g] = s;
+            l[g] *= alpha;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) o[g][e] *= alpha;
+          }
+          const float p = __builtin_amdgcn_exp2f(s - m[g]);
+          l[g] += p;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) o[g][e] = fmaf(p, vf[u][e], o[g][e]);
+        }
       }
     }
   }
@@ -206,23 +285,45 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(const T* __
   }
 }
 
-// grid (Hq, B), block D: merge the splits in index order, normalise, store.
+// grid (Hq, B), block kFinThreads: thread (j, d) merges splits j, j + NJ, ... in that order, then the NJ partial
+// states are merged in index order: a fixed order, whatever the launch.
+constexpr int kFinThreads = 512;
 template <typename T, int D>
-__global__ __launch_bounds__(D) void decode_finish_kernel(const float* __restrict__ part, int Hq, int splits,
-                                                          T* __restrict__ O, float* __restrict__ lse) {
-  const int hq = blockIdx.x, b = blockIdx.y, d = threadIdx.x;
+__global__ __launch_bounds__(kFinThreads) void decode_finish_kernel(const float* __restrict__ part, int Hq, int splits,
+                                                                    T* __restrict__ O, float* __restrict__ lse) {
+  constexpr int NJ = kFinThreads / D;
+  __shared__ float sm[NJ][D + 2];
+  const int hq = blockIdx.x, b = blockIdx.y, d = threadIdx.x % D, j = threadIdx.x / D;
   const float* src = part + ((size_t)b * Hq + hq) * splits * (D + 2);
   float mm = kNegBig;
-  for (int s = 0; s < splits; ++s) mm = fmaxf(mm, src[(size_t)s * (D + 2) + D]);
+  for (int s = j; s < splits; s += NJ) mm = fmaxf(mm, src[(size_t)s * (D + 2) + D]);
   float ll = 0.f, oo = 0.f;
-  for (int s = 0; s < splits; ++s) {
+  for (int s = j; s < splits; s += NJ) {
     const float* ps = src + (size_t)s * (D + 2);
     const float aw = __builtin_amdgcn_exp2f(ps[D] - mm);
     ll += ps[D + 1] * aw;
     oo += ps[d] * aw;
   }
-  DecElem<T>::store(O + ((size_t)b * Hq + hq) * D + d, ll > 0.f ? oo / ll : 0.f);
-  if (lse && d == 0) lse[(size_t)b * Hq + hq] = ll > 0.f ? mm * 0.6931471805599453f + logf(ll) : -INFINITY;
+  sm[j][d] = oo;
+  if (d == 0) {
+    sm[j][D] = mm;
+    sm[j][D + 1] = ll;
+  }
+  __syncthreads();
+  if (j == 0) {
+    float m2 = sm[0][D];
+#pragma unroll
+    for (int k = 1; k < NJ; ++k) m2 = fmaxf(m2, sm[k][D]);
+    float l2 = 0.f, o2 = 0.f;
+#pragma unroll
+    for (int k = 0; k < NJ; ++k) {
+      const float aw = __builtin_amdgcn_exp2f(sm[k][D] - m2);
+      l2 += sm[k][D + 1] * aw;
+      o2 += sm[k][d] * aw;
+    }
+    DecElem<T>::store(O + ((size_t)b * Hq + hq) * D + d, l2 > 0.f ? o2 / l2 : 0.f);
+    if (lse && d == 0) lse[(size_t)b * Hq + hq] = l2 > 0.f ? m2 * 0.6931471805599453f + logf(l2) : -INFINITY;
+  }
 }
 
 template <typename T, int D, int GP>
@@ -233,7 +334,7 @@ hipError_t launch_decode_gp(const void* q, const void* K, const void* V, void* O
   hipLaunchKernelGGL((decode_partial_kernel<T, D, GP>), dim3(splits, Hkv * chunks, B), dim3(kDecThreads), 0, s,
                      static_cast<const T*>(q), static_cast<const T*>(K), static_cast<const T*>(V), lens, S, Hq, Hkv, c2,
                      splits, part);
-  hipLaunchKernelGGL((decode_finish_kernel<T, D>), dim3(Hq, B), dim3(D), 0, s, part, Hq, splits, static_cast<T*>(O), lse);
+  hipLaunchKernelGGL((decode_finish_kernel<T, D>), dim3(Hq, B), dim3(kFinThreads), 0, s, part, Hq, splits, static_cast<T*>(O), lse);
   return hipGetLastError();
 }
 

@@ -130,6 +130,17 @@ seka_status seka_attention_plain(const void* Q, const void* K, const void* V, vo
                                  const seka_shape* sh, void* hip_stream);
 
 /*
+ * seka_attention_prefill_ragged — seka_attention_prefill for a padded batch of prompts of different lengths:
+ * prompt b has seq_lens[b] tokens (clamped to [0, S]); tokens at and beyond that index are padding: they are
+ * neither queries nor keys, and their rows of O and lse are left untouched.  The tensors keep their [B,S,...]
+ * layout (S = padded length).  seq_lens dev [B] int32, or NULL for seka_attention_prefill; st may be NULL for
+ * unsteered attention.
+ */
+seka_status seka_attention_prefill_ragged(const void* Q, const void* K, const void* V, void* O, float* lse,
+                                          const seka_shape* sh, const seka_steer* st, const int32_t* seq_lens,
+                                          void* hip_stream);
+
+/*
  * seka_attention_decode — the generation step after a steered prefill.  The edited keys persist in the KV
  * cache (run seka_edit_keys in place on the prompt's keys, the hook of Algorithm 1), so the new token's query
  * attends to the cache as it is: logits q . k_j / sqrt(d_k) over the first seq_lens[b] cached tokens (its own

@@ -59,6 +59,8 @@ lib.seka_decode_workspace_bytes.restype = _sz
 lib.seka_decode_workspace_bytes.argtypes = [_shape_p]
 lib.seka_attention_decode.restype = _i32
 lib.seka_attention_decode.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _shape_p, _vp, _sz, _vp]
+lib.seka_attention_prefill_ragged.restype = _i32
+lib.seka_attention_prefill_ragged.argtypes = [_vp, _vp, _vp, _vp, _vp, _shape_p, _steer_p, _vp, _vp]
 lib.seka_attention_plain.restype = _i32
 lib.seka_attention_plain.argtypes = [_vp, _vp, _vp, _vp, _vp, _shape_p, _vp]
 
@@ -191,4 +193,16 @@ def seka_attention_decode(q, K, V, O, seq_lens=None, lse=None, scale=0.0, worksp
     _check(lib.seka_attention_decode(_dev(q, "q"), _dev(K, "K"), _dev(V, "V"), _dev(O, "O"), _dev(lse, "lse"),
                                      _dev(seq_lens, "seq_lens"), ctypes.byref(sh), _dev(workspace, "workspace"),
                                      workspace.numel() * workspace.element_size(), _stream(stream)))
+    return O
+
+
+def seka_attention_prefill_ragged(Q, K, V, O, seq_lens, U=None, gain=None, mask=None, w=None, lse=None, scale=0.0,
+                                  stream=None, key_scale=None):
+    """Padded batch: seq_lens [B] int32 device tensor; U/gain/mask None for unsteered attention."""
+    B, S, Hq, D = Q.shape
+    Hkv = K.shape[2]
+    sh = _shape(B, S, Hq, Hkv, D, _dtype_code(Q), scale)
+    st = ctypes.byref(_steer(U, gain, mask, w, Hkv, key_scale)) if U is not None else None
+    _check(lib.seka_attention_prefill_ragged(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(O, "O"), _dev(lse, "lse"),
+                                             ctypes.byref(sh), st, _dev(seq_lens, "seq_lens"), _stream(stream)))
     return O

@@ -66,12 +66,13 @@ bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb) {
 }
 
 seka_status attention_common(const void* Q, const void* K, const void* V, void* O, float* lse,
-                             const seka_shape* sh, const seka_steer* st, void* hip_stream) {
+                             const seka_shape* sh, const seka_steer* st, const int32_t* seq_lens, void* hip_stream) {
   seka_status rc = check_shape(sh, true);
   if (rc != SEKA_OK) return rc;
   if (!Q || !K || !V || !O) return SEKA_ERR_NULL;
   if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || (lse && misaligned(lse)))
     return SEKA_ERR_ALIGN;
+  if (seq_lens && (reinterpret_cast<uintptr_t>(seq_lens) & 3u)) return SEKA_ERR_ALIGN;
   const size_t es = elem_size(sh->dtype);
   const size_t nq = (size_t)sh->B * sh->S * sh->Hq * sh->D * es;
   const size_t nk = (size_t)sh->B * sh->S * sh->Hkv * sh->D * es;
@@ -88,7 +89,7 @@ seka_status attention_common(const void* Q, const void* K, const void* V, void* 
   }
 
   seka::AttnArgs a;
-  a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse;
+  a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse; a.lens = seq_lens;
   a.B = sh->B; a.S = sh->S; a.Hq = sh->Hq; a.Hkv = sh->Hkv; a.D = sh->D;
   a.scale = sh->softmax_scale > 0.0f ? sh->softmax_scale : 1.0f / std::sqrt((float)sh->D);
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
@@ -201,12 +202,18 @@ seka_status seka_attention_decode(const void* q, const void* K, const void* V, v
 
 seka_status seka_attention_prefill(const void* Q, const void* K, const void* V, void* O, float* lse,
                                    const seka_shape* sh, const seka_steer* st, void* hip_stream) {
-  return attention_common(Q, K, V, O, lse, sh, st, hip_stream);
+  return attention_common(Q, K, V, O, lse, sh, st, nullptr, hip_stream);
 }
 
 seka_status seka_attention_plain(const void* Q, const void* K, const void* V, void* O, float* lse,
                                  const seka_shape* sh, void* hip_stream) {
-  return attention_common(Q, K, V, O, lse, sh, nullptr, hip_stream);
+  return attention_common(Q, K, V, O, lse, sh, nullptr, nullptr, hip_stream);
+}
+
+seka_status seka_attention_prefill_ragged(const void* Q, const void* K, const void* V, void* O, float* lse,
+                                          const seka_shape* sh, const seka_steer* st, const int32_t* seq_lens,
+                                          void* hip_stream) {
+  return attention_common(Q, K, V, O, lse, sh, st, seq_lens, hip_stream);
 }
 
 }  // extern "C"

@@ -31,7 +31,9 @@ __global__ __launch_bounds__(kThreads) void attention_f32_kernel(AttnArgs a, Ste
   const int q0 = (gridDim.x - 1 - blockIdx.x) * BQ;      // longest rows first
   const int row = threadIdx.x >> 2, part = threadIdx.x & 3;
   const int i = q0 + row;
-  const bool row_ok = i < a.S;
+  const int Sb = a.lens ? min(max(a.lens[b], 0), a.S) : a.S;      // this prompt's length (a.S stays the stride)
+  if (q0 >= Sb) return;                                  // block beyond the prompt's end (uniform, before any barrier)
+  const bool row_ok = i < Sb;
 
   float q[D];
   {
@@ -50,19 +52,19 @@ __global__ __launch_bounds__(kThreads) void attention_f32_kernel(AttnArgs a, Ste
   const int R = STEER ? st.M * st.r : 0;
   const float* Uh = STEER ? static_cast<const float*>(st.U) + (size_t)h * st.M * D * st.r : nullptr;
 
-  const int last_key = min(a.S, q0 + BQ) - 1;
+  const int last_key = min(Sb, q0 + BQ) - 1;
   for (int k0 = 0; k0 <= last_key; k0 += BK) {
     for (int idx = threadIdx.x; idx < BK * D; idx += kThreads) {
       const int jj = idx / D, d = idx % D, t = k0 + jj;
       const size_t off = (((size_t)b * a.S + t) * a.Hkv + h) * D + d;
-      Ks[jj][d] = t < a.S ? K[off] : 0.f;
-      Vs[jj][d] = t < a.S ? V[off] : 0.f;
+      Ks[jj][d] = t < Sb ? K[off] : 0.f;
+      Vs[jj][d] = t < Sb ? V[off] : 0.f;
     }
     int any = 0;
     if (STEER) {
       if (threadIdx.x < BK) {
         const int t = k0 + threadIdx.x;
-        const int mk = (t < a.S && gain != 0.f) ? st.mask[(size_t)b * a.S + t] : 0;
+        const int mk = (t < Sb && gain != 0.f) ? st.mask[(size_t)b * a.S + t] : 0;
         Ms[threadIdx.x] = mk;
         any = mk != 0;
       }

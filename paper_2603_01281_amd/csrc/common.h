@@ -32,6 +32,7 @@ struct AttnArgs {
   const void* V;
   void* O;
   float* lse;  // may be nullptr
+  const int* lens;  // dev [B] valid tokens per prompt (clamped to [0, S]), or nullptr for S everywhere
   int B, S, Hq, Hkv, D;
   float scale;
 };

@@ -21,7 +21,7 @@ def test_exports_every_declared_symbol(B):
     names = set(re.findall(r"\b(seka_[a-z_0-9]+)\s*\(", header))
     assert {"seka_route", "seka_edit_keys", "seka_attention_prefill", "seka_attention_plain",
             "seka_route_workspace_bytes", "seka_status_string", "seka_set_tuning",
-            "seka_attention_decode", "seka_decode_workspace_bytes"} <= names
+            "seka_attention_decode", "seka_decode_workspace_bytes", "seka_attention_prefill_ragged"} <= names
     for n in names:
         assert hasattr(B.lib, n), f"libseka.so does not export {n}"
 

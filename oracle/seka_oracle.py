@@ -21,6 +21,9 @@ What is written out here, in the order the paper states it:
                                                                      signed low-rank update, fed to edit_keys)
 * Sec. 2           Attn(i, j) = q_i . k_j / sqrt(d_k), causal softmax, weighted sum of V
                                                                   -> causal_attention
+* Sec. 3.1         Omega = h^T h+- / n, SVD, smallest k with leading-singular-value mass >= gamma
+                                                                  -> learn_projection
+* Sec. 3.4         D_h = mean_i || h+_i - h-_i ||_2               -> head_relevance_distance
 * generation step  the same attention for one new query per prompt over a cache of (edited) keys
                                                                   -> decode_attention
 * Eq. 6            alpha_m = sum_k (q.u_m^(k)) sigma_m^(k) / max_m |.|   -> route_eq6
@@ -230,6 +233,36 @@ def decode_attention(q, K, V, lens=None, scale=None):
             O[b, hq] = (e / e.sum()) @ v
             LSE[b, hq] = a_max + np.log(e.sum())
     return O, LSE
+
+
+def learn_projection(h_neutral, h_signal, gamma):
+    """Offline spectral learning for one layer (Sec. 3.1): per KV head, the cross-covariance
+    Omega = h^T h_signal / n of token key embeddings, its SVD Omega = U S V^T, and the smallest k whose
+    leading singular values hold at least a fraction gamma of their sum.
+
+    h_neutral, h_signal [n, H, d].  Returns U[H,d,d] (columns = left singular vectors, singular values
+    descending), S[H,d], k[H] (1 <= k <= d).  Eq. 2 then takes U[:, :k] (positive side) or U[:, k:] (negative).
+    """
+    hn = np.asarray(h_neutral, dtype=_F)
+    hs = np.asarray(h_signal, dtype=_F)
+    n, H, d = hn.shape
+    U = np.empty((H, d, d), dtype=_F)
+    S = np.empty((H, d), dtype=_F)
+    k = np.empty(H, dtype=np.int64)
+    for h in range(H):
+        omega = hn[:, h, :].T @ hs[:, h, :] / n
+        u, sv, _ = np.linalg.svd(omega)
+        U[h], S[h] = u, sv
+        frac = np.cumsum(sv) / sv.sum()
+        k[h] = int(np.searchsorted(frac, gamma - 1e-15) + 1)
+        k[h] = min(max(k[h], 1), d)
+    return U, S, k
+
+
+def head_relevance_distance(h_pos, h_neg):
+    """Sec. 3.4: D_h = mean over tokens of || h+_i - h-_i ||_2, per KV head.  h_pos, h_neg [n, H, d]."""
+    diff = np.asarray(h_pos, dtype=_F) - np.asarray(h_neg, dtype=_F)
+    return np.sqrt((diff * diff).sum(axis=-1)).mean(axis=0)
 
 
 def mean_group_query(Q, H, t0, t1):

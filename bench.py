@@ -151,6 +151,24 @@ def time_config(torch, seka, inputs, cfg, iters=10):
     return out
 
 
+def time_learn(torch, seka, inputs, n=16384, Hkv=8, D=128, iters=5):
+    """Offline stage for one layer of configuration 3's shape: n paired sample tokens per KV head."""
+    import numpy as np
+    ha, hb = inputs.paired_key_samples(n, Hkv, D, seed=3, dtype="bf16", rank=16, decay=0.85)
+    dev = lambda x: torch.from_numpy(x.view(np.int16)).view(torch.bfloat16).cuda().view(1, n, Hkv, D)
+    ha, hb = dev(ha), dev(hb)
+    U = torch.empty((Hkv, D, D), device="cuda")
+    sg = torch.empty((Hkv, D), device="cuda")
+    k = torch.empty((Hkv,), dtype=torch.int32, device="cuda")
+    Up = torch.empty((Hkv, D, 32), device="cuda", dtype=torch.bfloat16)
+    ws = torch.empty(1 << 24, dtype=torch.uint8, device="cuda")
+    dist = torch.empty((Hkv,), device="cuda")
+    learn_ms = event_time(torch, lambda: seka.seka_learn_projection(ha, hb, 0.9, U, sg, k, U_packed=Up, workspace=ws), iters)
+    dist_ms = event_time(torch, lambda: seka.seka_head_distance(ha, hb, dist, workspace=ws), iters)
+    return {"samples": n, "Hkv": Hkv, "D": D, "learn_projection_ms": round(learn_ms, 3), "rank_k": k.cpu().tolist(),
+            "head_distance_ms": round(dist_ms, 4), "head_distance_GBps": round(2 * ha.numel() * 2 / dist_ms / 1e6, 1)}
+
+
 def paired_medians(torch, fn_a, fn_b, flops, n=15):
     for _ in range(max(10, int(120.0 / (flops / 1.0e12)))):      # ~1 PFLOP/s => ms per launch ~ flops / 1e12
         fn_a()
@@ -252,6 +270,7 @@ def main():
         del src, dst
     if args.extras:
         out["other_configs"] = {f"cfg{c}": time_config(torch, seka, inputs, c) for c in (2, 3, 4, 5)}
+        out["offline_learn"] = time_learn(torch, seka, inputs)
     del layers
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:

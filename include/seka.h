@@ -159,6 +159,39 @@ seka_status seka_attention_decode(const void* q, const void* K, const void* V, v
                                   const int32_t* seq_lens, const seka_shape* sh, void* workspace,
                                   size_t workspace_bytes, void* hip_stream);
 
+/*
+ * seka_learn_projection — the offline stage for one layer (paper Sec. 3.1): per KV head, the cross-covariance
+ * Omega_h = h_neutral^T h_signal / n of token key embeddings sampled under a neutral and under a relevant
+ * (or irrelevant) context, its singular value decomposition Omega = U Sigma V^T, and the rank k_h that keeps a
+ * share gamma of the singular-value mass (Eq. 3: the smallest k with sum_{i<=k} sigma_i >= gamma sum_i sigma_i).
+ * The positive projector of Eq. 2 is P = U[:, :k] U[:, :k]^T; for the negative projector pass the irrelevant
+ * samples as h_signal and keep the trailing columns U[:, k:].
+ *
+ * h_neutral, h_signal  dev [B,S,Hkv,D] tensor dtype: n = B*S paired sample tokens (row t of both is the same
+ *                      token under the two contexts); n < 2^24.
+ * gamma      in (0, 1].
+ * U_out      dev [Hkv,D,D] fp32: column c of U_out[h] is the left singular vector of the c-th largest singular
+ *            value (unit norm, sign unspecified).  Where sigma_c <= 1e-5 sigma_1 no direction is determined in
+ *            fp32 and the column is all zero; vectors of equal singular values span the right subspace only.
+ * sigma_out  dev [Hkv,D] fp32, descending.
+ * k_out      dev [Hkv] int32, in [1, D].
+ * U_packed   dev [Hkv,D,r_pad] tensor dtype or NULL: the first min(k_h, r_pad) columns of U_out[h], the remaining
+ *            columns zero, ready to be seka_steer.U with M = 1, r = r_pad (1 <= r_pad <= D).
+ * workspace  dev scratch of at least seka_learn_workspace_bytes(sh) bytes, 16-byte aligned.
+ * fp32 arithmetic throughout (one-sided Jacobi iteration to a relative off-diagonal of 2e-6); deterministic.
+ *
+ * seka_head_distance — the head-selection score of Sec. 3.4: D_out[h] = (1/n) sum_t || h_pos[t,h,:] -
+ * h_neg[t,h,:] ||_2 over the n = B*S sample tokens; heads whose score clears a threshold are given a nonzero
+ * gain by the caller.  h_pos, h_neg dev [B,S,Hkv,D] tensor dtype; D_out dev [Hkv] fp32; workspace as above
+ * (seka_learn_workspace_bytes covers both calls).  Deterministic.
+ */
+size_t seka_learn_workspace_bytes(const seka_shape* sh);
+seka_status seka_learn_projection(const void* h_neutral, const void* h_signal, const seka_shape* sh, float gamma,
+                                  float* U_out, float* sigma_out, int32_t* k_out, void* U_packed, int32_t r_pad,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream);
+seka_status seka_head_distance(const void* h_pos, const void* h_neg, const seka_shape* sh, float* D_out,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* Name of a status code; static storage, never NULL. */
 const char* seka_status_string(int32_t status);
 

@@ -61,6 +61,12 @@ lib.seka_attention_decode.restype = _i32
 lib.seka_attention_decode.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _shape_p, _vp, _sz, _vp]
 lib.seka_attention_prefill_ragged.restype = _i32
 lib.seka_attention_prefill_ragged.argtypes = [_vp, _vp, _vp, _vp, _vp, _shape_p, _steer_p, _vp, _vp]
+lib.seka_learn_workspace_bytes.restype = _sz
+lib.seka_learn_workspace_bytes.argtypes = [_shape_p]
+lib.seka_learn_projection.restype = _i32
+lib.seka_learn_projection.argtypes = [_vp, _vp, _shape_p, _f32, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]
+lib.seka_head_distance.restype = _i32
+lib.seka_head_distance.argtypes = [_vp, _vp, _shape_p, _vp, _vp, _sz, _vp]
 lib.seka_attention_plain.restype = _i32
 lib.seka_attention_plain.argtypes = [_vp, _vp, _vp, _vp, _vp, _shape_p, _vp]
 
@@ -206,3 +212,35 @@ def seka_attention_prefill_ragged(Q, K, V, O, seq_lens, U=None, gain=None, mask=
     _check(lib.seka_attention_prefill_ragged(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(O, "O"), _dev(lse, "lse"),
                                              ctypes.byref(sh), st, _dev(seq_lens, "seq_lens"), _stream(stream)))
     return O
+
+
+def seka_learn_projection(h_neutral, h_signal, gamma, U_out, sigma_out, k_out, U_packed=None, workspace=None,
+                          stream=None):
+    """h_* [B,S,Hkv,D]; U_out [Hkv,D,D] fp32, sigma_out [Hkv,D] fp32, k_out [Hkv] int32; U_packed [Hkv,D,r_pad]."""
+    torch = _torch()
+    B, S, Hkv, D = h_neutral.shape
+    sh = _shape(B, S, Hkv, Hkv, D, _dtype_code(h_neutral), 0.0)
+    need = lib.seka_learn_workspace_bytes(ctypes.byref(sh))
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=h_neutral.device)
+    r_pad = U_packed.shape[2] if U_packed is not None else 0
+    _check(lib.seka_learn_projection(_dev(h_neutral, "h_neutral"), _dev(h_signal, "h_signal"), ctypes.byref(sh),
+                                     float(gamma), _dev(U_out, "U_out"), _dev(sigma_out, "sigma_out"),
+                                     _dev(k_out, "k_out"), _dev(U_packed, "U_packed"), r_pad,
+                                     _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
+                                     _stream(stream)))
+    return U_out, sigma_out, k_out
+
+
+def seka_head_distance(h_pos, h_neg, D_out, workspace=None, stream=None):
+    """h_* [B,S,Hkv,D]; D_out [Hkv] fp32."""
+    torch = _torch()
+    B, S, Hkv, D = h_pos.shape
+    sh = _shape(B, S, Hkv, Hkv, D, _dtype_code(h_pos), 0.0)
+    if workspace is None:
+        workspace = torch.empty(max(lib.seka_learn_workspace_bytes(ctypes.byref(sh)), 16), dtype=torch.uint8,
+                                device=h_pos.device)
+    _check(lib.seka_head_distance(_dev(h_pos, "h_pos"), _dev(h_neg, "h_neg"), ctypes.byref(sh), _dev(D_out, "D_out"),
+                                  _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
+                                  _stream(stream)))
+    return D_out

@@ -11,7 +11,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libseka.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
-SOURCES = ["api.hip", "route.hip", "edit.hip", "decode.hip", "attn_f32.hip", "attn_bf16.hip", "attn_bf16_d128.hip", "attn_bf16_d64.hip",
+SOURCES = ["api.hip", "route.hip", "edit.hip", "decode.hip", "learn.hip", "attn_f32.hip", "attn_bf16.hip", "attn_bf16_d128.hip", "attn_bf16_d64.hip",
            "attn_bf16_pipe_plain.hip", "attn_bf16_pipe_r32.hip", "attn_bf16_pipe_r64.hip", "attn_bf16_pipe_r128.hip"]
 
 FLAGS = [

@@ -200,6 +200,65 @@ seka_status seka_attention_decode(const void* q, const void* K, const void* V, v
   return launch_status(e);
 }
 
+size_t seka_learn_workspace_bytes(const seka_shape* sh) {
+  if (check_shape(sh, false) != SEKA_OK || (int64_t)sh->B * sh->S >= (1 << 24)) return 0;
+  return seka::learn_workspace_bytes(sh->Hkv, sh->D, sh->B * sh->S);
+}
+
+seka_status seka_learn_projection(const void* h_neutral, const void* h_signal, const seka_shape* sh, float gamma,
+                                  float* U_out, float* sigma_out, int32_t* k_out, void* U_packed, int32_t r_pad,
+                                  void* workspace, size_t workspace_bytes, void* hip_stream) {
+  seka_status rc = check_shape(sh, false);
+  if (rc != SEKA_OK) return rc;
+  if ((int64_t)sh->B * sh->S >= (1 << 24)) return SEKA_ERR_SHAPE;
+  if (!h_neutral || !h_signal || !U_out || !sigma_out || !k_out) return SEKA_ERR_NULL;
+  if (!(gamma > 0.0f && gamma <= 1.0f)) return SEKA_ERR_SHAPE;
+  if (U_packed && (r_pad < 1 || r_pad > sh->D)) return SEKA_ERR_SHAPE;
+  if (misaligned(h_neutral) || misaligned(h_signal) || misaligned(U_out) || misaligned(sigma_out) ||
+      (U_packed && misaligned(U_packed)) || (reinterpret_cast<uintptr_t>(k_out) & 3u))
+    return SEKA_ERR_ALIGN;
+  const int n = sh->B * sh->S;
+  const size_t nh = (size_t)n * sh->Hkv * sh->D * elem_size(sh->dtype);
+  const size_t nu = (size_t)sh->Hkv * sh->D * sh->D * sizeof(float), ns = (size_t)sh->Hkv * sh->D * sizeof(float);
+  const void* outs[4] = {U_out, sigma_out, k_out, U_packed};
+  const size_t out_bytes[4] = {nu, ns, (size_t)sh->Hkv * sizeof(int32_t),
+                               U_packed ? (size_t)sh->Hkv * sh->D * r_pad * elem_size(sh->dtype) : 0};
+  for (int i = 0; i < 4; ++i) {
+    if (!out_bytes[i]) continue;
+    if (ranges_overlap(outs[i], out_bytes[i], h_neutral, nh) || ranges_overlap(outs[i], out_bytes[i], h_signal, nh))
+      return SEKA_ERR_ALIAS;
+    for (int j = i + 1; j < 4; ++j)
+      if (out_bytes[j] && ranges_overlap(outs[i], out_bytes[i], outs[j], out_bytes[j])) return SEKA_ERR_ALIAS;
+  }
+  const size_t need = seka::learn_workspace_bytes(sh->Hkv, sh->D, n);
+  if (!workspace || workspace_bytes < need) return SEKA_ERR_WORKSPACE;
+  if (misaligned(workspace)) return SEKA_ERR_ALIGN;
+  (void)hipGetLastError();
+  hipError_t e = seka::launch_learn(h_neutral, h_signal, n, sh->Hkv, sh->D, sh->dtype, gamma, U_out, sigma_out, k_out,
+                                    U_packed, r_pad, workspace, reinterpret_cast<hipStream_t>(hip_stream));
+  return launch_status(e);
+}
+
+seka_status seka_head_distance(const void* h_pos, const void* h_neg, const seka_shape* sh, float* D_out,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+  seka_status rc = check_shape(sh, false);
+  if (rc != SEKA_OK) return rc;
+  if ((int64_t)sh->B * sh->S >= (1 << 24)) return SEKA_ERR_SHAPE;
+  if (!h_pos || !h_neg || !D_out) return SEKA_ERR_NULL;
+  if (misaligned(h_pos) || misaligned(h_neg) || (reinterpret_cast<uintptr_t>(D_out) & 3u)) return SEKA_ERR_ALIGN;
+  const int n = sh->B * sh->S;
+  const size_t nh = (size_t)n * sh->Hkv * sh->D * elem_size(sh->dtype);
+  if (ranges_overlap(D_out, (size_t)sh->Hkv * sizeof(float), h_pos, nh) ||
+      ranges_overlap(D_out, (size_t)sh->Hkv * sizeof(float), h_neg, nh))
+    return SEKA_ERR_ALIAS;
+  if (!workspace || workspace_bytes < seka::learn_workspace_bytes(sh->Hkv, sh->D, n)) return SEKA_ERR_WORKSPACE;
+  if (misaligned(workspace)) return SEKA_ERR_ALIGN;
+  (void)hipGetLastError();
+  hipError_t e = seka::launch_head_distance(h_pos, h_neg, n, sh->Hkv, sh->D, sh->dtype, D_out, workspace,
+                                            reinterpret_cast<hipStream_t>(hip_stream));
+  return launch_status(e);
+}
+
 seka_status seka_attention_prefill(const void* Q, const void* K, const void* V, void* O, float* lse,
                                    const seka_shape* sh, const seka_steer* st, void* hip_stream) {
   return attention_common(Q, K, V, O, lse, sh, st, nullptr, hip_stream);

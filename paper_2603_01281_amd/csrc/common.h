@@ -52,6 +52,12 @@ size_t decode_workspace_bytes(int B, int S, int Hq, int Hkv, int D);
 hipError_t launch_decode(const void* q, const void* K, const void* V, void* O, float* lse, const int* lens, int B, int S,
                          int Hq, int Hkv, int D, int dtype, float scale, void* workspace, hipStream_t s);
 
+size_t learn_workspace_bytes(int Hkv, int D, int n);
+hipError_t launch_learn(const void* hn, const void* hs, int n, int Hkv, int D, int dtype, float gamma, float* U_out,
+                        float* sigma_out, int* k_out, void* U_packed, int r_pad, void* workspace, hipStream_t s);
+hipError_t launch_head_distance(const void* hp, const void* hm, int n, int Hkv, int D, int dtype, float* D_out,
+                                void* workspace, hipStream_t s);
+
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
 }  // namespace seka

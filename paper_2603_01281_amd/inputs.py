@@ -38,7 +38,7 @@ def _rng(seed, stream):
 
 
 # stream ids, one per tensor kind (layer index is added in the upper bits)
-_STREAM = {"Q": 1, "K": 2, "V": 3, "U": 4, "mask": 5, "proto": 6, "gain": 7, "sigma": 8, "svd": 9}
+_STREAM = {"Q": 1, "K": 2, "V": 3, "U": 4, "mask": 5, "proto": 6, "gain": 7, "sigma": 8, "svd": 9, "samples": 10}
 
 
 def _stream(kind, layer=0):
@@ -121,6 +121,26 @@ def singular_vector_sets(Hkv, D, seed, layer=0):
 def store(x, dtype):
     """float array -> storage form of `dtype` ("f32": float32, "bf16": uint16 bit patterns, round to nearest even)."""
     return _store(np.asarray(x, dtype=np.float32), dtype)
+
+
+def paired_key_samples(n, Hkv, D, seed, dtype, rank=12, decay=0.8, noise=0.05, shift=0.5, layer=0):
+    """Stand-ins for the key embeddings of n sample tokens under two contexts (paper Sec. 3.1: the same
+    tokens seen with a neutral and with a relevant prompt).  Per KV head a `rank`-dimensional latent code z_t
+    drives both views through two different orthonormal frames, component i scaled by decay**i, so the
+    cross-covariance has `rank` well separated leading singular values over a noise floor; the second view
+    also carries a constant offset (the context's mean shift).  Returns (h_a, h_b), storage form, [n, Hkv, D]."""
+    g = _rng(seed, _stream("samples", layer))
+    z = g.standard_normal(size=(n, Hkv, rank))
+    amp = 2.0 * decay ** np.arange(rank)
+    fa = np.empty((Hkv, D, rank))
+    fb = np.empty((Hkv, D, rank))
+    for h in range(Hkv):
+        fa[h] = np.linalg.qr(g.standard_normal(size=(D, rank)))[0]
+        fb[h] = np.linalg.qr(g.standard_normal(size=(D, rank)))[0]
+    ha = np.einsum("nhk,hdk->nhd", z * amp, fa) + noise * g.standard_normal(size=(n, Hkv, D))
+    hb = np.einsum("nhk,hdk->nhd", z, fb) + noise * g.standard_normal(size=(n, Hkv, D))
+    hb += shift * g.standard_normal(size=(1, Hkv, D)) / np.sqrt(D)
+    return _store(ha.astype(np.float32), dtype), _store(hb.astype(np.float32), dtype)
 
 
 def unit_prototypes(Hkv, M, D, seed, layer=0):

@@ -21,7 +21,8 @@ def test_exports_every_declared_symbol(B):
     names = set(re.findall(r"\b(seka_[a-z_0-9]+)\s*\(", header))
     assert {"seka_route", "seka_edit_keys", "seka_attention_prefill", "seka_attention_plain",
             "seka_route_workspace_bytes", "seka_status_string", "seka_set_tuning",
-            "seka_attention_decode", "seka_decode_workspace_bytes", "seka_attention_prefill_ragged"} <= names
+            "seka_attention_decode", "seka_decode_workspace_bytes", "seka_attention_prefill_ragged",
+            "seka_learn_workspace_bytes", "seka_learn_projection", "seka_head_distance"} <= names
     for n in names:
         assert hasattr(B.lib, n), f"libseka.so does not export {n}"
 
@@ -131,3 +132,37 @@ def test_decode_rejects_bad_arguments(B):
     assert call(FAKE, far, w=None) == 8
     assert call(FAKE, far, wb=need - 1) == 8
     assert L.seka_decode_workspace_bytes(ctypes.byref(_shape(B, Hq=5))) == 0
+
+
+def test_learn_rejects_bad_arguments(B):
+    L = B.lib
+    ok = _shape(B)
+    need = L.seka_learn_workspace_bytes(ctypes.byref(ok))
+    assert need > 0 and need % 16 == 0
+    big = 1 << 32                                     # far apart: no two fake ranges overlap
+    hn, hs, U, sg, k, ws = (FAKE + i * big for i in range(6))
+
+    def call(hn=hn, hs=hs, sh=ok, gamma=0.9, U=U, sg=sg, k=k, Up=None, r_pad=0, ws=ws, wb=need):
+        return L.seka_learn_projection(hn, hs, ctypes.byref(sh), gamma, U, sg, k, Up, r_pad, ws, wb, None)
+    assert call(hn=None) == 1
+    assert call(k=None) == 1
+    assert call(gamma=0.0) == 2
+    assert call(gamma=1.5) == 2
+    assert call(gamma=float("nan")) == 2
+    assert call(sh=_shape(B, D=96)) == 2
+    assert call(Up=FAKE + 7 * big, r_pad=0) == 2
+    assert call(Up=FAKE + 7 * big, r_pad=129) == 2
+    assert call(U=U + 4) == 4
+    assert call(k=k + 2) == 4
+    assert call(U=hn) == 5                            # an output over an input
+    assert call(sg=U) == 5                            # two outputs over each other
+    assert call(ws=None) == 8
+    assert call(wb=need - 1) == 8
+    hd = lambda hp=hn, hm=hs, out=U, sh=ok, w=ws, wb=need: L.seka_head_distance(hp, hm, ctypes.byref(sh), out, w, wb, None)
+    assert hd(hp=None) == 1
+    assert hd(out=None) == 1
+    assert hd(out=U + 2) == 4
+    assert hd(out=hn) == 5
+    assert hd(w=None) == 8
+    assert hd(wb=15) == 8
+    assert hd(sh=_shape(B, dtype=7)) == 3

@@ -17,14 +17,19 @@
 //     are a register plus an immediate (the loop is unrolled over the three ring stages so that stage
 //     offsets are compile-time constants), tile loads take a scalar base plus a per-lane offset computed
 //     once, the row maximum uses three-input max, the row sum uses the bf16 dot-product instruction;
-//   * MFMAs and vector instructions alternate in program order: iteration t issues the S^T products of
-//     the next 32-key block interleaved with the softmax of the current block, then the PV products of
-//     the current block interleaved with their transposing LDS reads.
+//   * MFMAs and vector instructions alternate in program order, and every MFMA has vector work beside it:
+//     a step handles three consecutive 32-key blocks at once: the S^T products of the next block, the softmax
+//     of the current one and the PV products of the previous one (whose probabilities were formed one step
+//     earlier), so the exponentials are spread over twelve MFMAs instead of four.
 // The softmax runs per 32-key block (half a tile), which halves the score registers the pipeline needs.
-// K and V tiles live in rings of three LDS stages; K(t+2) and V(t+2) are requested at the top of
-// iteration t and K(t+2) is edited (highlighted keys only) at the bottom of iteration t.
+// K tiles live in a ring of three LDS stages; V in a ring of six half tiles that runs half a tile behind K
+// (see the tile loads).  K(t+2) and the V blocks 2t+3, 2t+4 are requested at the top of iteration t and K(t+2)
+// is edited (highlighted keys only) at the bottom of iteration t.
 #pragma once
 #include <type_traits>
+#ifndef SEKA_B_SCHED
+#define SEKA_B_SCHED 1
+#endif
 
 #include "attn_bf16_lds_dma.h"
 
@@ -151,49 +156,72 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   const uint32_t rowbytes = (uint32_t)a.Hkv * D * 2;
   const uint32_t kst_base = (uint32_t)(uintptr_t)(dma_lds_void_ptr)Kst;
   const uint32_t vst_base = (uint32_t)(uintptr_t)(dma_lds_void_ptr)Vst;
+  // V travels in units of half a tile, one half tile behind K: "shifted tile" t = rows [64 t - 32, 64 t + 32) = the
+  // 32-key blocks 2t - 1 and 2t, and block j lives at ring position j % 6 (8 KB each; tile t = positions 2t % 6,
+  // 2t % 6 + 1 as before).  The PV product of a block runs one step after its softmax (see `step`), so the last
+  // block of tile t is still being read while the loads of iteration t + 1 are in flight; shifting the unit by
+  // half a tile makes every load overwrite only blocks that all waves are done with.
+  constexpr int HB = TB / 2;              // bytes of a 32-key block
   int slot_row[SPW];          // first LDS row of this lane in slot n
-  uint32_t koff[SPW], voff[SPW], slot_lds[SPW];
+  uint32_t koff[SPW], voff[SPW], slot_lds[SPW], vslot_lds[SPW];
+  bool vslot_hi[SPW];         // slot n belongs to the second block of a shifted tile (wave-uniform)
 #pragma unroll
   for (int n = 0; n < SPW; ++n) {
     const int slot = min(wave + NW * n, SLOTS - 1);      // surplus slots repeat the last one (same bytes)
     const int row = 4 * slot + (lane >> 4);
     slot_row[n] = row;
     slot_lds[n] = 1024u * slot;
+    vslot_lds[n] = 1024u * (slot & (SLOTS / 2 - 1));
+    vslot_hi[n] = slot >= SLOTS / 2;
     koff[n] = row * rowbytes + 16u * ((lane & 15) ^ (row & 15));
     voff[n] = row * rowbytes + 16u * ((lane & 15) ^ (4 * (row & 3)));
   }
-  const unsigned char* kv_head = nullptr;   // unused; keeps the two bases below symmetric
-  (void)kv_head;
   const size_t head_off = ((size_t)b * Scap * a.Hkv + h) * D * 2;          // bytes to this (batch, KV head), token 0
   const unsigned char* Kbytes = reinterpret_cast<const unsigned char*>(Kg) + head_off;
   const unsigned char* Vbytes = reinterpret_cast<const unsigned char*>(Vg) + head_off;
-  auto issue_rows = [&](auto full_c, const unsigned char* tensor, int t, uint32_t lds_stage_base,
-                        const uint32_t (&off)[SPW]) __attribute__((always_inline)) {
-    const unsigned char* tile = tensor + (size_t)t * BK * rowbytes;
+  // ring position (byte offset inside the V ring) of 32-key block j >= -1
+  auto vpos = [&](int j) __attribute__((always_inline)) -> uint32_t { return (uint32_t)((j + 6) % 6) * HB; };
+  // K tile t into its ring stage.  `full`: every row of the tile exists (no clamping, offsets fixed per lane).
+  // Otherwise rows past the prompt's end repeat its last key (finite data that the causal mask hides); offsets
+  // are then taken from token 0 so that they never go negative.
+  auto issue_k_to = [&](auto full_c, int t, uint32_t lds_stage_base) __attribute__((always_inline)) {
     if (decltype(full_c)::value || t * BK + BK <= S) {
+      const unsigned char* tile = Kbytes + (size_t)t * BK * rowbytes;
 #pragma unroll
-      for (int n = 0; n < SPW; ++n) pipe_load_16B(tile, off[n], lds_stage_base + slot_lds[n]);
+      for (int n = 0; n < SPW; ++n) pipe_load_16B(tile, koff[n], lds_stage_base + slot_lds[n]);
     } else {
-      const int last_row = S - 1 - t * BK;             // rows past the end repeat the last key (finite data)
 #pragma unroll
       for (int n = 0; n < SPW; ++n)
-        pipe_load_16B(tile, off[n] - (uint32_t)max(0, slot_row[n] - last_row) * rowbytes, lds_stage_base + slot_lds[n]);
+        pipe_load_16B(Kbytes, koff[n] + (uint32_t)(min(t * BK + slot_row[n], S - 1) - slot_row[n]) * rowbytes,
+                      lds_stage_base + slot_lds[n]);
     }
   };
-  auto issue_k = [&](int t) __attribute__((always_inline)) {
-    issue_rows(std::false_type{}, Kbytes, t, kst_base + (t % 3) * TB, koff);
+  // Shifted V tile t: block 2t - 1 to ring byte offset posA, block 2t to posB.
+  auto issue_v_to = [&](auto full_c, int t, uint32_t posA, uint32_t posB) __attribute__((always_inline)) {
+    const int first = t * BK - BK / 2;
+    if (decltype(full_c)::value || (first >= 0 && first + BK <= S)) {
+      const unsigned char* tile = Vbytes + (size_t)first * rowbytes;
+#pragma unroll
+      for (int n = 0; n < SPW; ++n) pipe_load_16B(tile, voff[n], vst_base + (vslot_hi[n] ? posB : posA) + vslot_lds[n]);
+    } else {
+#pragma unroll
+      for (int n = 0; n < SPW; ++n)
+        pipe_load_16B(Vbytes, voff[n] + (uint32_t)(min(max(first + slot_row[n], 0), S - 1) - slot_row[n]) * rowbytes,
+                      vst_base + (vslot_hi[n] ? posB : posA) + vslot_lds[n]);
+    }
   };
-  auto issue_v = [&](int t) __attribute__((always_inline)) {
-    issue_rows(std::false_type{}, Vbytes, t, vst_base + (t % 3) * TB, voff);
-  };
+  auto issue_k = [&](int t) __attribute__((always_inline)) { issue_k_to(std::false_type{}, t, kst_base + (t % 3) * TB); };
+  auto issue_v = [&](int t) __attribute__((always_inline)) { issue_v_to(std::false_type{}, t, vpos(2 * t - 1), vpos(2 * t)); };
 
   // ---- Q fragments: B operand of S^T = K Q^T, lane (col = row qi, k = 16 ks + 8 hf + e) ----
   bf16x8 qf[RPW][KS];
-  // First loads of a block of query rows: K/V tiles 0 and 1, then the wave's Q rows.
+  // First loads of a block of query rows: K tiles 0 and 1, V blocks -1 (a copy of row 0: the first step's PV
+  // product multiplies it by zero probabilities, so it only has to be finite) to 2, then the wave's Q rows.
   auto begin_block = [&]() __attribute__((always_inline)) {
     issue_k(0);
     issue_v(0);
-    if (ntiles > 1) { issue_k(1); issue_v(1); }
+    if (ntiles > 1) issue_k(1);
+    issue_v(1);
 #pragma unroll
     for (int rp = 0; rp < RPW; ++rp) {
       const int qi = qi0 + 32 * rp;
@@ -292,7 +320,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     auto ustage = [&](int d, int chunk) __attribute__((always_inline)) -> unsigned char* {
       const int sw = CPR == 16 ? (d & 15) : ((d >> 1) & 7);
       const int off = d * (Rpad * 2) + 16 * (chunk ^ sw);
-      return off < TB ? Kst + 2 * TB + off : Vst + 2 * TB + (off - TB);
+      return off < TB ? Kst + 2 * TB + off : Vst + 3 * HB + (off - TB);
     };
     auto place = [&](int m, int d, int v, const uint4 val) __attribute__((always_inline)) {
       if (DENSE) {
@@ -332,7 +360,8 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     }
     if (DENSE) {
       // Dense form.  U_cat (row d, r contiguous, zero-padded to Rpad columns) is staged in the third stage of
-      // the two tile rings, which no tile load touches before the main loop starts; 16-byte chunks of a row are
+      // the K ring and positions 3 and 4 of the V ring, which no tile load touches before the main loop starts
+      // (the first loads fill V positions 5, 0, 1 and 2); 16-byte chunks of a row are
       // swizzled so that sixteen consecutive rows can be read at one chunk index without bank conflicts.
       const int padc = CPR - R / 8;                    // R is a multiple of 8
       for (int idx = tid; idx < D * padc; idx += NT)
@@ -529,7 +558,13 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
     return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
   };
-  // Raise the reference exponent of the rows whose maximum ran away from it, and rescale their sums and outputs.
+  // Raise the reference exponent of the rows whose maximum ran away from it, and rescale their sums.  The output
+  // accumulators are rescaled by rescale_outputs(), which the caller runs once every PV product whose
+  // probabilities were formed against the old reference has been accumulated.
+  float alpha_pend[RPW];
+  bool rescale_pend[RPW];                // wave-uniform
+#pragma unroll
+  for (int rp = 0; rp < RPW; ++rp) { alpha_pend[rp] = 1.f; rescale_pend[rp] = false; }
   auto raise_reference = [&](int rp, float mfull) __attribute__((always_inline)) {
     const bool need = mfull > m_run[rp] + kSlack;
     if (__any(need)) {   // a handful of times per row
@@ -537,11 +572,20 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
       const float alpha = __builtin_amdgcn_exp2f(m_run[rp] - m_new);
       m_run[rp] = m_new;
       l_run[rp] *= alpha;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) oacc[rp][db][r] *= alpha;
+      alpha_pend[rp] = alpha;            // rescale_outputs() has run since the last raise of this row block
+      rescale_pend[rp] = true;
     }
+  };
+  auto rescale_outputs = [&]() __attribute__((always_inline)) {
+#pragma unroll
+    for (int rp = 0; rp < RPW; ++rp)
+      if (rescale_pend[rp]) {
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) oacc[rp][db][r] *= alpha_pend[rp];
+        rescale_pend[rp] = false;
+      }
   };
   // Second part: probabilities, packed P^T, row sum of the rounded probabilities (the values the PV product uses).
   auto block_exp = [&](int rp, f32x16& sv, bf16x8 (&pb)[2]) __attribute__((always_inline)) {
@@ -617,6 +661,11 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     tile_evt = next_event(1);
   }
 
+  bf16x8 pb[RPW][2];           // probabilities (P^T operand) of the block whose PV product is next; none at first
+#pragma unroll
+  for (int rp = 0; rp < RPW; ++rp)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { pb[rp][0][e] = (__bf16)0.f; pb[rp][1][e] = (__bf16)0.f; }
   f32x16 sc0[RPW], sc1[RPW];   // scores of keys 0..31 / 32..63 of the current tile, per row block
 #pragma unroll
   for (int rp = 0; rp < RPW; ++rp)
@@ -628,25 +677,25 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     for (int rp = 0; rp < RPW; ++rp) pipe_mfma_result_guard(sc0[rp]);
   }
 
-  // Top of iteration t: request K(t+2) and V(t+2) (in this order).  Bottom: K(t+2) and V(t+1) must have landed
-  // before the next iteration (V(t+2) stays in flight); then edit K(t+2) if it holds highlighted keys.
+  // Top of iteration t: request K(t+2), then the V blocks 2t+3 and 2t+4.  Bottom: everything but those two V
+  // blocks must have landed before the next iteration; then edit K(t+2) if it holds highlighted keys.
   // The hot loop only runs where tile t + 2 exists and is complete (`sure`): no tests there.
   auto top = [&](auto sure_c, auto stage_c, int t) __attribute__((always_inline)) {
     constexpr bool SURE = decltype(sure_c)::value;
     if (SURE) {
-      constexpr int ST2 = (decltype(stage_c)::value + 2) % 3;
-      issue_rows(std::true_type{}, Kbytes, t + 2, kst_base + ST2 * TB, koff);
-      issue_rows(std::true_type{}, Vbytes, t + 2, vst_base + ST2 * TB, voff);
-    } else if (t + 2 < ntiles) {
-      issue_k(t + 2);
-      issue_v(t + 2);
+      constexpr int ST = decltype(stage_c)::value;          // = t % 3
+      issue_k_to(std::true_type{}, t + 2, kst_base + ((ST + 2) % 3) * TB);
+      issue_v_to(std::true_type{}, t + 2, ((2 * ST + 3) % 6) * HB, ((2 * ST + 4) % 6) * HB);
+    } else if (t + 1 < ntiles) {
+      if (t + 2 < ntiles) issue_k(t + 2);
+      issue_v(t + 2);                                       // its first block belongs to tile t + 1
     }
   };
   auto bottom = [&](auto sure_c, int t) __attribute__((always_inline)) {
 #ifdef SEKA_CYCLE_PROBE
     const unsigned long long w0 = __builtin_amdgcn_s_memtime();
 #endif
-    if (decltype(sure_c)::value || t + 2 < ntiles) dma_wait_vmcnt<SPW>();
+    if (decltype(sure_c)::value || t + 1 < ntiles) dma_wait_vmcnt<SPW>();   // all but the V loads of this iteration
     else dma_wait_vmcnt<0>();
 #ifdef SEKA_CYCLE_PROBE
     const unsigned long long w1 = __builtin_amdgcn_s_memtime();
@@ -679,13 +728,15 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     }
   };
 
-  // One software-pipelined step: the S^T block at LDS offset KOFF is produced into `next` while the softmax of
-  // `cur` runs on the vector ALU; then the PV products of `cur` (V rows at LDS offset VOFF).
+  // One software-pipelined step over three consecutive 32-key blocks: the S^T block at LDS offset KOFF is
+  // produced into `next` and the PV products of the block before `cur` (probabilities pb, V rows at ring offset
+  // VOFF) are accumulated while the softmax of `cur` runs on the vector ALU; pb then receives the probabilities
+  // of `cur`.  Every MFMA of the step has vector work to share the issue port with.
   // The LDS offsets are std::integral_constant in the main loop (they become immediates) and int elsewhere.
-  auto step = [&](auto koff_c, auto voff_c, f32x16 (&cur)[RPW], f32x16 (&next)[RPW]) __attribute__((always_inline)) {
+  auto step = [&](auto koff_c, auto voff_c, f32x16 (&cur)[RPW], f32x16 (&next)[RPW], bf16x8 (&pb)[RPW][2]) __attribute__((always_inline)) {
     const int KOFF = koff_c, VOFF = voff_c;
     constexpr int NM = (KS / 2) * RPW;            // MFMAs per half of the S^T block
-    bf16x8 pb[RPW][2];
+    bf16x8 pn[RPW][2];
     float mfull[RPW];
     // (a) first half of the products, interleaved with the row maxima
     qk_part(IC0{}, ICH{}, KOFF, next);
@@ -703,53 +754,69 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int rp = 0; rp < RPW; ++rp) raise_reference(rp, mfull[rp]);
-    // (b) second half of the products, interleaved with the exponentials
+    // (b) second half of the products and the PV products of the previous block, interleaved with the exponentials
     qk_part(ICH{}, ICK{}, KOFF, next);
+    pv_half(VOFF, pb);
 #pragma unroll
-    for (int rp = 0; rp < RPW; ++rp) block_exp(rp, cur[rp], pb[rp]);
+    for (int rp = 0; rp < RPW; ++rp) block_exp(rp, cur[rp], pn[rp]);
     if (SCHED == 1) {
       __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
 #pragma unroll
       for (int i = 0; i < NM; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
         if (i % RPW == 0 && i / RPW < KS / 2 - 2) __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
-        __builtin_amdgcn_sched_group_barrier(0x002, 12, 1);
+        if (i == NM - 1) __builtin_amdgcn_sched_group_barrier(0x100, 4, 1);      // first V operands
+        __builtin_amdgcn_sched_group_barrier(0x002, 4, 1);
       }
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    // (c) the PV products of the current block with their transposing reads
-    pv_half(VOFF, pb);
-    if (SCHED == 1) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 4, 2);
 #pragma unroll
       for (int i = 0; i < 2 * DB; ++i) {
 #pragma unroll
-        for (int rp = 0; rp < RPW; ++rp) __builtin_amdgcn_sched_group_barrier(0x008, 1, 2);
-        if (i < 2 * DB - 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 2);
+        for (int rp = 0; rp < RPW; ++rp) {
+          __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
+          if (rp == 0 && i < 2 * DB - 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+          __builtin_amdgcn_sched_group_barrier(0x002, 5, 1);
+        }
       }
     }
+    // The probabilities are first used by the next step: without a use here their whole computation is sunk
+    // into that step, away from the MFMAs it is meant to share the issue port with.
+#pragma unroll
+    for (int rp = 0; rp < RPW; ++rp) asm volatile("" : "+v"(pn[rp][0]), "+v"(pn[rp][1]), "+v"(l_run[rp]));
     __builtin_amdgcn_sched_barrier(0);
+    rescale_outputs();
+#pragma unroll
+    for (int rp = 0; rp < RPW; ++rp) { pb[rp][0] = pn[rp][0]; pb[rp][1] = pn[rp][1]; }
   };
   // One tile every row of this wave sees in full; ST = t % 3 is compile-time so that every LDS read address is
-  // a register plus an immediate.  Enters with S(t, keys 0..31) in sc0, leaves with S(t+1, keys 0..31) in sc0.
+  // a register plus an immediate.  Enters with S(t, keys 0..31) in sc0 and the probabilities of the block before
+  // it in pb; leaves with the same for tile t + 1.
   auto hot = [&](auto st_c, int t) __attribute__((always_inline)) {
     constexpr int ST = decltype(st_c)::value;
     using std::integral_constant;
+    // The operand addresses pass through an opaque copy once per tile: otherwise every "address + stage offset"
+    // below is hoisted out of the loop into a register of its own (dozens), instead of being an immediate.
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(kaddr[ks]));
+#pragma unroll
+    for (int db = 0; db < DB; ++db) asm volatile("" : "+v"(vaddr[db]));
     top(std::true_type{}, st_c, t);
-    step(integral_constant<int, ST * TB + 32 * 256>{}, integral_constant<int, ST * TB>{}, sc0, sc1);
-    step(integral_constant<int, ((ST + 1) % 3) * TB>{}, integral_constant<int, ST * TB + 32 * 256>{}, sc1, sc0);
+    step(integral_constant<int, ST * TB + HB>{}, integral_constant<int, ((2 * ST + 5) % 6) * HB>{}, sc0, sc1, pb);
+    step(integral_constant<int, ((ST + 1) % 3) * TB>{}, integral_constant<int, 2 * ST * HB>{}, sc1, sc0, pb);
     bottom(std::true_type{}, t);
   };
 
   // Hot iterations: tile t is seen in full by every row of this wave, and tile t + 2 exists and is complete.
   const int t_hot = min(tw_last, min(ntiles, S / BK) - 2);
   int t = 0;
-  if (t_hot > 0) {
+  {
     using std::integral_constant;
-    for (;;) {
-      hot(integral_constant<int, 0>{}, t); if (++t == t_hot) break;
-      hot(integral_constant<int, 1>{}, t); if (++t == t_hot) break;
-      hot(integral_constant<int, 2>{}, t); if (++t == t_hot) break;
+    // whole turns of the ring only: a single loop exit (exits after every tile made the compiler park the values
+    // the code after the loop needs in scratch memory, inside the loop); the remainder runs below
+#pragma nounroll
+    for (; t + 3 <= t_hot; t += 3) {
+      hot(integral_constant<int, 0>{}, t);
+      hot(integral_constant<int, 1>{}, t + 1);
+      hot(integral_constant<int, 2>{}, t + 2);
     }
   }
 #ifdef SEKA_CYCLE_PROBE
@@ -760,37 +827,51 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   for (; t < tw_last; ++t) {
     top(std::false_type{}, IC0{}, t);
     const int off = (t % 3) * TB, offn = ((t + 1) % 3) * TB;
-    step(off + 32 * 256, off, sc0, sc1);
-    step(offn, off + 32 * 256, sc1, sc0);
+    step(off + HB, (int)vpos(2 * t - 1), sc0, sc1, pb);
+    step(offn, (int)vpos(2 * t), sc1, sc0, pb);
     bottom(std::false_type{}, t);
   }
-  // ---- the wave's last tile (causal mask, nothing further to score), then idle turns while other waves finish ----
+  // ---- the wave's last tile (causal mask, nothing further to score), then idle turns while other waves finish.
+  // The second block of that tile may still be in flight during its own iteration (V runs half a tile behind), so
+  // its PV product waits for the barrier at the bottom: it is done one turn later, or after the loop. ----
+  bool owed = false;                       // wave-uniform: pb holds probabilities whose PV product is outstanding
+  int owed_off = 0;
 #pragma nounroll
   for (; t < ntiles; ++t) {
     top(std::false_type{}, IC0{}, t);
+    if (owed) {
+      pv_half(owed_off, pb);
+      owed = false;
+    }
     if (t == tw_last) {
       const int off = (t % 3) * TB;
-      bf16x8 pb[RPW][2];
-      qk_part(IC0{}, ICK{}, off + 32 * 256, sc1);
+      qk_part(IC0{}, ICK{}, off + HB, sc1);
+      if (t > 0) pv_half((int)vpos(2 * t - 1), pb);      // the block before this tile (its softmax ran in the last step)
 #pragma unroll
       for (int rp = 0; rp < RPW; ++rp) {
         pipe_mfma_result_guard(sc0[rp]);
         causal_mask(t * BK, rp, sc0[rp]);
         raise_reference(rp, block_max(sc0[rp]));
-        block_exp(rp, sc0[rp], pb[rp]);
       }
-      pv_half(off, pb);
+      rescale_outputs();
+#pragma unroll
+      for (int rp = 0; rp < RPW; ++rp) block_exp(rp, sc0[rp], pb[rp]);
+      pv_half((int)vpos(2 * t), pb);
 #pragma unroll
       for (int rp = 0; rp < RPW; ++rp) {
         pipe_mfma_result_guard(sc1[rp]);
         causal_mask(t * BK + 32, rp, sc1[rp]);
         raise_reference(rp, block_max(sc1[rp]));
-        block_exp(rp, sc1[rp], pb[rp]);
       }
-      pv_half(off + 32 * 256, pb);
+      rescale_outputs();
+#pragma unroll
+      for (int rp = 0; rp < RPW; ++rp) block_exp(rp, sc1[rp], pb[rp]);
+      owed = true;
+      owed_off = (int)vpos(2 * t + 1);
     }
     bottom(std::false_type{}, t);
   }
+  if (owed) pv_half(owed_off, pb);
 
 #ifdef SEKA_CYCLE_PROBE
   if (a.lse && lane == 0 && qi0 < S) {
@@ -808,11 +889,12 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   prb_edit = prb_n = prb_wait = prb_bar = 0ull;
   prb_entry = __builtin_amdgcn_s_memtime();
 #endif
-  // ---- next block's first loads (every wave is past the last barrier: the tile rings are free), then this
+  // ---- next block's first loads (after a barrier: the last PV product above still read the V ring), then this
   // block's output ----
   const int qi_out = qi0;
   const bool more = pass + 1 < npass;
   if (more) {
+    dma_barrier();
     qb = pair;
     qw = qb * BQ + WR * (wave % RBW);
     qi0 = qw + l32;

@@ -671,11 +671,14 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   for (int rp = 0; rp < RPW; ++rp)
 #pragma unroll
     for (int r = 0; r < 16; ++r) { sc0[rp][r] = 0.f; sc1[rp][r] = 0.f; }
+  bf16x8 kpre[2];              // first two K fragments of the block the next step scores (see `step`)
   if (0 <= tw_last) {
     qk_part(IC0{}, ICK{}, 0, sc0);
 #pragma unroll
     for (int rp = 0; rp < RPW; ++rp) pipe_mfma_result_guard(sc0[rp]);
   }
+#pragma unroll
+  for (int i = 0; i < 2; ++i) kpre[i] = *(pipe_lds_bf16x8_ptr)(uintptr_t)(kaddr[i] + HB);
 
   // Top of iteration t: request K(t+2), then the V blocks 2t+3 and 2t+4.  Bottom: everything but those two V
   // blocks must have landed before the next iteration; then edit K(t+2) if it holds highlighted keys.
@@ -733,21 +736,41 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   // VOFF) are accumulated while the softmax of `cur` runs on the vector ALU; pb then receives the probabilities
   // of `cur`.  Every MFMA of the step has vector work to share the issue port with.
   // The LDS offsets are std::integral_constant in the main loop (they become immediates) and int elsewhere.
-  auto step = [&](auto koff_c, auto voff_c, f32x16 (&cur)[RPW], f32x16 (&next)[RPW], bf16x8 (&pb)[RPW][2]) __attribute__((always_inline)) {
-    const int KOFF = koff_c, VOFF = voff_c;
-    constexpr int NM = (KS / 2) * RPW;            // MFMAs per half of the S^T block
+  // kpre: the first two K fragments of the block at KOFF, read during the previous step (an LDS read issued right
+  // before the MFMA that needs it leaves the wave waiting for the whole LDS latency); on return it holds those of
+  // the block at KNEXT, the one the following step scores.
+  auto kfrag = [&](int ks, int off) __attribute__((always_inline)) -> bf16x8 {
+    return *(pipe_lds_bf16x8_ptr)(uintptr_t)(kaddr[ks] + off);
+  };
+  auto qk_one = [&](int ks, const bf16x8& a0, f32x16 (&sn)[RPW]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int rp = 0; rp < RPW; ++rp) sn[rp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[rp][ks], sn[rp], 0, 0, 0);
+  };
+  auto step = [&](auto koff_c, auto knext_c, auto voff_c, f32x16 (&cur)[RPW], f32x16 (&next)[RPW], bf16x8 (&pb)[RPW][2],
+                  bf16x8 (&kpre)[2]) __attribute__((always_inline)) {
+    static_assert(KS == 8, "the fragment schedule below is written for eight k-slices");
+    const int KOFF = koff_c, KNEXT = knext_c, VOFF = voff_c;
     bf16x8 pn[RPW][2];
     float mfull[RPW];
-    // (a) first half of the products, interleaved with the row maxima
-    qk_part(IC0{}, ICH{}, KOFF, next);
+    // (a) first half of the products, interleaved with the row maxima; fragments 4 and 5 are requested here
+#pragma unroll
+    for (int rp = 0; rp < RPW; ++rp)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) next[rp][r] = 0.f;
+    qk_one(0, kpre[0], next);
+    qk_one(1, kpre[1], next);
+    const bf16x8 k2 = kfrag(2, KOFF), k3 = kfrag(3, KOFF);
+    qk_one(2, k2, next);
+    qk_one(3, k3, next);
+    const bf16x8 k4 = kfrag(4, KOFF), k5 = kfrag(5, KOFF);
 #pragma unroll
     for (int rp = 0; rp < RPW; ++rp) mfull[rp] = block_max(cur[rp]);
     if (SCHED == 1) {
       __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
 #pragma unroll
-      for (int i = 0; i < NM; ++i) {
+      for (int i = 0; i < 4 * RPW; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (i % RPW == 0 && i / RPW < KS / 2 - 2) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+        if (i == 1 * RPW || i == 2 * RPW) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
         __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
       }
     }
@@ -755,17 +778,22 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 #pragma unroll
     for (int rp = 0; rp < RPW; ++rp) raise_reference(rp, mfull[rp]);
     // (b) second half of the products and the PV products of the previous block, interleaved with the exponentials
-    qk_part(ICH{}, ICK{}, KOFF, next);
+    qk_one(4, k4, next);
+    qk_one(5, k5, next);
+    const bf16x8 k6 = kfrag(6, KOFF), k7 = kfrag(7, KOFF);
+    qk_one(6, k6, next);
+    qk_one(7, k7, next);
     pv_half(VOFF, pb);
+    kpre[0] = kfrag(0, KNEXT);
+    kpre[1] = kfrag(1, KNEXT);
 #pragma unroll
     for (int rp = 0; rp < RPW; ++rp) block_exp(rp, cur[rp], pn[rp]);
     if (SCHED == 1) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+      __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);       // fragments 6 and 7
 #pragma unroll
-      for (int i = 0; i < NM; ++i) {
+      for (int i = 0; i < 4 * RPW; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
-        if (i % RPW == 0 && i / RPW < KS / 2 - 2) __builtin_amdgcn_sched_group_barrier(0x100, 1, 1);
-        if (i == NM - 1) __builtin_amdgcn_sched_group_barrier(0x100, 4, 1);      // first V operands
+        if (i >= 2 * RPW - 1 && i % RPW == RPW - 1) __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);   // V operands, two MFMAs ahead
         __builtin_amdgcn_sched_group_barrier(0x002, 4, 1);
       }
 #pragma unroll
@@ -773,7 +801,8 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 #pragma unroll
         for (int rp = 0; rp < RPW; ++rp) {
           __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
-          if (rp == 0 && i < 2 * DB - 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+          if (rp == 0 && i < 2 * DB - 3) __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
+          if (rp == 0 && i == 2 * DB - 3) __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);     // the next block's first fragments
           __builtin_amdgcn_sched_group_barrier(0x002, 5, 1);
         }
       }
@@ -782,6 +811,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     // into that step, away from the MFMAs it is meant to share the issue port with.
 #pragma unroll
     for (int rp = 0; rp < RPW; ++rp) asm volatile("" : "+v"(pn[rp][0]), "+v"(pn[rp][1]), "+v"(l_run[rp]));
+    asm volatile("" : "+v"(kpre[0]), "+v"(kpre[1]));
     __builtin_amdgcn_sched_barrier(0);
     rescale_outputs();
 #pragma unroll
@@ -800,8 +830,8 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 #pragma unroll
     for (int db = 0; db < DB; ++db) asm volatile("" : "+v"(vaddr[db]));
     top(std::true_type{}, st_c, t);
-    step(integral_constant<int, ST * TB + HB>{}, integral_constant<int, ((2 * ST + 5) % 6) * HB>{}, sc0, sc1, pb);
-    step(integral_constant<int, ((ST + 1) % 3) * TB>{}, integral_constant<int, 2 * ST * HB>{}, sc1, sc0, pb);
+    step(integral_constant<int, ST * TB + HB>{}, integral_constant<int, ((ST + 1) % 3) * TB>{}, integral_constant<int, ((2 * ST + 5) % 6) * HB>{}, sc0, sc1, pb, kpre);
+    step(integral_constant<int, ((ST + 1) % 3) * TB>{}, integral_constant<int, ((ST + 1) % 3) * TB + HB>{}, integral_constant<int, 2 * ST * HB>{}, sc1, sc0, pb, kpre);
     bottom(std::true_type{}, t);
   };
 
@@ -827,8 +857,8 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   for (; t < tw_last; ++t) {
     top(std::false_type{}, IC0{}, t);
     const int off = (t % 3) * TB, offn = ((t + 1) % 3) * TB;
-    step(off + HB, (int)vpos(2 * t - 1), sc0, sc1, pb);
-    step(offn, (int)vpos(2 * t), sc1, sc0, pb);
+    step(off + HB, offn, (int)vpos(2 * t - 1), sc0, sc1, pb, kpre);
+    step(offn, offn + HB, (int)vpos(2 * t), sc1, sc0, pb, kpre);
     bottom(std::false_type{}, t);
   }
   // ---- the wave's last tile (causal mask, nothing further to score), then idle turns while other waves finish.

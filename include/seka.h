@@ -141,6 +141,24 @@ seka_status seka_attention_prefill_ragged(const void* Q, const void* K, const vo
                                           void* hip_stream);
 
 /*
+ * seka_attention_prefill_packed — seka_attention_prefill for a batch stored without padding (the "varlen"
+ * layout of serving stacks): the prompts' tokens follow one another in tensors of total_tokens rows, prompt b
+ * owning rows [cu_seqlens[b], cu_seqlens[b+1]).
+ *
+ * Q, O      dev [total_tokens,Hq,D];  K, V dev [total_tokens,Hkv,D];  st->mask dev [total_tokens];
+ * lse       dev [Hq,total_tokens] fp32 or NULL;  st->w stays [B,Hkv,M] (one set of coefficients per prompt).
+ * sh->B     number of prompts; sh->S an upper bound of the longest prompt (it sizes the launch; longer prompts
+ *           are cut to sh->S tokens).
+ * cu_seqlens dev [B+1] int32, non-decreasing, cu_seqlens[0] = 0 expected; values are clamped into
+ *           [0, total_tokens] on the device, so no content of it can make the kernels leave the tensors.
+ * st may be NULL for unsteered attention.  Rows of O / lse that belong to no prompt are left untouched.
+ * (seka_edit_keys serves this layout as B = 1, S = total_tokens when w is NULL; seka_route per prompt.)
+ */
+seka_status seka_attention_prefill_packed(const void* Q, const void* K, const void* V, void* O, float* lse,
+                                          const seka_shape* sh, const seka_steer* st, const int32_t* cu_seqlens,
+                                          int64_t total_tokens, void* hip_stream);
+
+/*
  * seka_attention_decode — the generation step after a steered prefill.  The edited keys persist in the KV
  * cache (run seka_edit_keys in place on the prompt's keys, the hook of Algorithm 1), so the new token's query
  * attends to the cache as it is: logits q . k_j / sqrt(d_k) over the first seq_lens[b] cached tokens (its own

@@ -67,6 +67,8 @@ lib.seka_learn_projection.restype = _i32
 lib.seka_learn_projection.argtypes = [_vp, _vp, _shape_p, _f32, _vp, _vp, _vp, _vp, _i32, _vp, _sz, _vp]
 lib.seka_head_distance.restype = _i32
 lib.seka_head_distance.argtypes = [_vp, _vp, _shape_p, _vp, _vp, _sz, _vp]
+lib.seka_attention_prefill_packed.restype = _i32
+lib.seka_attention_prefill_packed.argtypes = [_vp, _vp, _vp, _vp, _vp, _shape_p, _steer_p, _vp, ctypes.c_int64, _vp]
 lib.seka_attention_plain.restype = _i32
 lib.seka_attention_plain.argtypes = [_vp, _vp, _vp, _vp, _vp, _shape_p, _vp]
 
@@ -244,3 +246,18 @@ def seka_head_distance(h_pos, h_neg, D_out, workspace=None, stream=None):
                                   _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
                                   _stream(stream)))
     return D_out
+
+
+def seka_attention_prefill_packed(Q, K, V, O, cu_seqlens, max_len, U=None, gain=None, mask=None, w=None, lse=None,
+                                  scale=0.0, stream=None, key_scale=None):
+    """Unpadded batch: Q/O [total,Hq,D], K/V [total,Hkv,D], mask [total], lse [Hq,total]; cu_seqlens [B+1] int32
+    device tensor; max_len >= the longest prompt.  U/gain/mask None for unsteered attention."""
+    total, Hq, D = Q.shape
+    Hkv = K.shape[1]
+    B = cu_seqlens.numel() - 1
+    sh = _shape(B, max_len, Hq, Hkv, D, _dtype_code(Q), scale)
+    st = ctypes.byref(_steer(U, gain, mask, w, Hkv, key_scale)) if U is not None else None
+    _check(lib.seka_attention_prefill_packed(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(O, "O"), _dev(lse, "lse"),
+                                             ctypes.byref(sh), st, _dev(cu_seqlens, "cu_seqlens"), total,
+                                             _stream(stream)))
+    return O

@@ -65,17 +65,22 @@ bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb) {
   return x < y + nb && y < x + na;
 }
 
+// seq_lens: padded batch with per-prompt lengths; cu_seqlens (with total_tokens): packed batch; at most one of them.
 seka_status attention_common(const void* Q, const void* K, const void* V, void* O, float* lse,
-                             const seka_shape* sh, const seka_steer* st, const int32_t* seq_lens, void* hip_stream) {
+                             const seka_shape* sh, const seka_steer* st, const int32_t* seq_lens,
+                             const int32_t* cu_seqlens, int64_t total_tokens, void* hip_stream) {
   seka_status rc = check_shape(sh, true);
   if (rc != SEKA_OK) return rc;
   if (!Q || !K || !V || !O) return SEKA_ERR_NULL;
   if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O) || (lse && misaligned(lse)))
     return SEKA_ERR_ALIGN;
   if (seq_lens && (reinterpret_cast<uintptr_t>(seq_lens) & 3u)) return SEKA_ERR_ALIGN;
+  if (cu_seqlens && (reinterpret_cast<uintptr_t>(cu_seqlens) & 3u)) return SEKA_ERR_ALIGN;
+  if (cu_seqlens && (total_tokens < 1 || total_tokens > 0x7fffffffLL)) return SEKA_ERR_SHAPE;
   const size_t es = elem_size(sh->dtype);
-  const size_t nq = (size_t)sh->B * sh->S * sh->Hq * sh->D * es;
-  const size_t nk = (size_t)sh->B * sh->S * sh->Hkv * sh->D * es;
+  const size_t tokens = cu_seqlens ? (size_t)total_tokens : (size_t)sh->B * sh->S;
+  const size_t nq = tokens * sh->Hq * sh->D * es;
+  const size_t nk = tokens * sh->Hkv * sh->D * es;
   if (ranges_overlap(O, nq, Q, nq) || ranges_overlap(O, nq, K, nk) || ranges_overlap(O, nq, V, nk))
     return SEKA_ERR_ALIAS;
 
@@ -90,6 +95,7 @@ seka_status attention_common(const void* Q, const void* K, const void* V, void* 
 
   seka::AttnArgs a;
   a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse; a.lens = seq_lens;
+  a.cu = cu_seqlens; a.total = cu_seqlens ? (int)total_tokens : 0;
   a.B = sh->B; a.S = sh->S; a.Hq = sh->Hq; a.Hkv = sh->Hkv; a.D = sh->D;
   a.scale = sh->softmax_scale > 0.0f ? sh->softmax_scale : 1.0f / std::sqrt((float)sh->D);
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
@@ -261,18 +267,25 @@ seka_status seka_head_distance(const void* h_pos, const void* h_neg, const seka_
 
 seka_status seka_attention_prefill(const void* Q, const void* K, const void* V, void* O, float* lse,
                                    const seka_shape* sh, const seka_steer* st, void* hip_stream) {
-  return attention_common(Q, K, V, O, lse, sh, st, nullptr, hip_stream);
+  return attention_common(Q, K, V, O, lse, sh, st, nullptr, nullptr, 0, hip_stream);
 }
 
 seka_status seka_attention_plain(const void* Q, const void* K, const void* V, void* O, float* lse,
                                  const seka_shape* sh, void* hip_stream) {
-  return attention_common(Q, K, V, O, lse, sh, nullptr, nullptr, hip_stream);
+  return attention_common(Q, K, V, O, lse, sh, nullptr, nullptr, nullptr, 0, hip_stream);
 }
 
 seka_status seka_attention_prefill_ragged(const void* Q, const void* K, const void* V, void* O, float* lse,
                                           const seka_shape* sh, const seka_steer* st, const int32_t* seq_lens,
                                           void* hip_stream) {
-  return attention_common(Q, K, V, O, lse, sh, st, seq_lens, hip_stream);
+  return attention_common(Q, K, V, O, lse, sh, st, seq_lens, nullptr, 0, hip_stream);
+}
+
+seka_status seka_attention_prefill_packed(const void* Q, const void* K, const void* V, void* O, float* lse,
+                                          const seka_shape* sh, const seka_steer* st, const int32_t* cu_seqlens,
+                                          int64_t total_tokens, void* hip_stream) {
+  if (!cu_seqlens) return SEKA_ERR_NULL;
+  return attention_common(Q, K, V, O, lse, sh, st, nullptr, cu_seqlens, total_tokens, hip_stream);
 }
 
 }  // extern "C"

@@ -85,7 +85,9 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
   const int qb = nQB - 1 - (int)(blockIdx.x / per_qb);
   const int rem = blockIdx.x % per_qb;
   const int b = rem / nHC, hc = rem % nHC;
-  const int S = a.lens ? min(max(a.lens[b], 0), Scap) : Scap;      // this prompt's length
+  size_t tok0;                               // first token of this prompt in the tensors
+  int S;                                     // this prompt's length
+  prompt_extent(a, b, tok0, S);
   if (qb * BQ >= S) return;                  // block beyond the prompt's end (workgroup-uniform, before any barrier)
   const int hq0 = hc * HPW;
   const int h = hq0 / G;
@@ -104,7 +106,7 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
   bf16x8 qf[KS];
   {
     const bool ok = qi < S;
-    const uint16_t* qp = Qg + (((size_t)b * Scap + (ok ? qi : 0)) * a.Hq + hq) * D + 8 * hf;
+    const uint16_t* qp = Qg + ((tok0 + (ok ? qi : 0)) * a.Hq + hq) * D + 8 * hf;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       uint4 v = make_uint4(0, 0, 0, 0);
@@ -152,14 +154,14 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
       const int key = t * BK + row;
       uint4 v = make_uint4(0, 0, 0, 0);
       if ((NCH * NT == CHUNKS || c < CHUNKS) && key < S)
-        v = *reinterpret_cast<const uint4*>(src + (((size_t)b * Scap + key) * a.Hkv + h) * D + 8 * cc);
+        v = *reinterpret_cast<const uint4*>(src + ((tok0 + key) * a.Hkv + h) * D + 8 * cc);
       dst[n] = v;
     }
   };
   auto load_mask = [&](int t) {
     if (STEER && steer_on) {
       const int key = t * BK + lane;
-      mpre = key < S ? st.mask[(size_t)b * Scap + key] : 0;
+      mpre = key < S ? st.mask[tok0 + key] : 0;
     }
   };
   auto store_rows = [&](uint16_t* dst, int ld, const uint4 (&src)[NCH]) {
@@ -462,7 +464,7 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
   const float l_tot = l_run + __shfl_xor(l_run, 32);
   if (qi < S) {
     const float inv = 1.f / l_tot;
-    uint16_t* op = Og + (((size_t)b * Scap + qi) * a.Hq + hq) * D + 4 * hf;
+    uint16_t* op = Og + ((tok0 + qi) * a.Hq + hq) * D + 4 * hf;
 #pragma unroll
     for (int db = 0; db < DB; ++db) {
 #pragma unroll
@@ -473,7 +475,7 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
         *reinterpret_cast<uint2*>(op + 32 * db + 8 * q4) = __builtin_bit_cast(uint2, o4);
       }
     }
-    if (a.lse && hf == 0) a.lse[((size_t)b * a.Hq + hq) * Scap + qi] = m_run * a.scale + logf(l_tot);
+    if (a.lse && hf == 0) a.lse[lse_index(a, b, hq, tok0, qi)] = m_run * a.scale + logf(l_tot);
   }
 }
 

@@ -127,7 +127,9 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   const int b = rem / nHC, hc = rem % nHC;
   const int hq0 = hc * HPW;
   const int h = hq0 / G;
-  const int S = a.lens ? min(max(a.lens[b], 0), Scap) : Scap;      // this prompt's length: rows and keys beyond it do not exist
+  size_t tok0;                               // first token of this prompt in the tensors
+  int S;                                     // this prompt's length: rows and keys beyond it do not exist
+  prompt_extent(a, b, tok0, S);
   int npass = (nQB - 1 - pair != pair) ? 2 : 1;
   int qb = nQB - 1 - pair;
   if (qb * BQ >= S) {                        // the later block lies beyond this prompt's end
@@ -176,7 +178,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     koff[n] = row * rowbytes + 16u * ((lane & 15) ^ (row & 15));
     voff[n] = row * rowbytes + 16u * ((lane & 15) ^ (4 * (row & 3)));
   }
-  const size_t head_off = ((size_t)b * Scap * a.Hkv + h) * D * 2;          // bytes to this (batch, KV head), token 0
+  const size_t head_off = (tok0 * a.Hkv + h) * D * 2;          // bytes to this (batch, KV head), token 0
   const unsigned char* Kbytes = reinterpret_cast<const unsigned char*>(Kg) + head_off;
   const unsigned char* Vbytes = reinterpret_cast<const unsigned char*>(Vg) + head_off;
   // ring position (byte offset inside the V ring) of 32-key block j >= -1
@@ -226,7 +228,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     for (int rp = 0; rp < RPW; ++rp) {
       const int qi = qi0 + 32 * rp;
       const bool ok = qi < S;
-      const uint16_t* qp = Qg + (((size_t)b * Scap + (ok ? qi : 0)) * a.Hq + hq) * D + 8 * hf;
+      const uint16_t* qp = Qg + ((tok0 + (ok ? qi : 0)) * a.Hq + hq) * D + 8 * hf;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks)     // rows past the end read row 0 (finite data, results never stored):
         qf[rp][ks] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(qp + 16 * ks));   // no branch, no wait here
@@ -245,7 +247,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     constexpr int UB = 4;                             // pieces per thread and turn
 
     // (1) mask bytes of tile `tid` (first turn of the bitmap loop), if the fast form applies
-    const uint8_t* mrow = st.mask + (size_t)b * Scap;
+    const uint8_t* mrow = st.mask + tok0;
     const int nfull = S / BK;
     const bool wide = (reinterpret_cast<uintptr_t>(mrow) & 15) == 0 && nfull > 0;
     uint4 mv0[BK / 16];
@@ -905,7 +907,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 
 #ifdef SEKA_CYCLE_PROBE
   if (a.lse && lane == 0 && qi0 < S) {
-    float* dp = a.lse + ((size_t)b * a.Hq + hq) * Scap + qi0;
+    float* dp = a.lse + lse_index(a, b, hq, tok0, qi0);
     dp[0] = (float)(prb_start - prb_entry);                          // set-up until the first tiles are usable
     dp[1] = (float)(__builtin_amdgcn_s_memtime() - prb_start);       // loops of this block
     dp[2] = (float)(__builtin_amdgcn_s_memrealtime() - prb_rstart);  // the same span in 100 MHz ticks
@@ -941,7 +943,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     const float l_tot = l_run[rp] + __shfl_xor(l_run[rp], 32);
     if (qi < S) {
       const float inv = 1.f / l_tot;
-      uint16_t* op = Og + (((size_t)b * Scap + qi) * a.Hq + hq) * D + 4 * hf;
+      uint16_t* op = Og + ((tok0 + qi) * a.Hq + hq) * D + 4 * hf;
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
 #pragma unroll
@@ -954,7 +956,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
       }
 #ifndef SEKA_CYCLE_PROBE
       // m_run is the reference exponent in units of s * scale * log2(e); l_tot is relative to it
-      if (a.lse && hf == 0) a.lse[((size_t)b * a.Hq + hq) * Scap + qi] = m_run[rp] * 0.6931471805599453f + logf(l_tot);
+      if (a.lse && hf == 0) a.lse[lse_index(a, b, hq, tok0, qi)] = m_run[rp] * 0.6931471805599453f + logf(l_tot);
 #endif
     }
   }

@@ -31,13 +31,15 @@ __global__ __launch_bounds__(kThreads) void attention_f32_kernel(AttnArgs a, Ste
   const int q0 = (gridDim.x - 1 - blockIdx.x) * BQ;      // longest rows first
   const int row = threadIdx.x >> 2, part = threadIdx.x & 3;
   const int i = q0 + row;
-  const int Sb = a.lens ? min(max(a.lens[b], 0), a.S) : a.S;      // this prompt's length (a.S stays the stride)
+  size_t tok0;                                           // first token of this prompt in the tensors
+  int Sb;                                                // this prompt's length
+  prompt_extent(a, b, tok0, Sb);
   if (q0 >= Sb) return;                                  // block beyond the prompt's end (uniform, before any barrier)
   const bool row_ok = i < Sb;
 
   float q[D];
   {
-    const float* qp = Q + (((size_t)b * a.S + (row_ok ? i : 0)) * a.Hq + hq) * D;
+    const float* qp = Q + ((tok0 + (row_ok ? i : 0)) * a.Hq + hq) * D;
 #pragma unroll
     for (int d = 0; d < D; ++d) q[d] = row_ok ? qp[d] : 0.f;
   }
@@ -56,7 +58,7 @@ __global__ __launch_bounds__(kThreads) void attention_f32_kernel(AttnArgs a, Ste
   for (int k0 = 0; k0 <= last_key; k0 += BK) {
     for (int idx = threadIdx.x; idx < BK * D; idx += kThreads) {
       const int jj = idx / D, d = idx % D, t = k0 + jj;
-      const size_t off = (((size_t)b * a.S + t) * a.Hkv + h) * D + d;
+      const size_t off = ((tok0 + t) * a.Hkv + h) * D + d;
       Ks[jj][d] = t < Sb ? K[off] : 0.f;
       Vs[jj][d] = t < Sb ? V[off] : 0.f;
     }
@@ -64,7 +66,7 @@ __global__ __launch_bounds__(kThreads) void attention_f32_kernel(AttnArgs a, Ste
     if (STEER) {
       if (threadIdx.x < BK) {
         const int t = k0 + threadIdx.x;
-        const int mk = (t < Sb && gain != 0.f) ? st.mask[(size_t)b * a.S + t] : 0;
+        const int mk = (t < Sb && gain != 0.f) ? st.mask[tok0 + t] : 0;
         Ms[threadIdx.x] = mk;
         any = mk != 0;
       }
@@ -135,11 +137,11 @@ __global__ __launch_bounds__(kThreads) void attention_f32_kernel(AttnArgs a, Ste
   l_run += __shfl_xor(l_run, 1);
   l_run += __shfl_xor(l_run, 2);
   if (row_ok) {
-    float* op = O + (((size_t)b * a.S + i) * a.Hq + hq) * D + part * DP;
+    float* op = O + ((tok0 + i) * a.Hq + hq) * D + part * DP;
     const float inv = 1.f / l_run;
 #pragma unroll
     for (int d = 0; d < DP; ++d) op[d] = o[d] * inv;
-    if (a.lse && part == 0) a.lse[((size_t)b * a.Hq + hq) * a.S + i] = m_run + logf(l_run);
+    if (a.lse && part == 0) a.lse[lse_index(a, b, hq, tok0, i)] = m_run + logf(l_run);
   }
 }
 

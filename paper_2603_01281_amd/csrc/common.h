@@ -33,7 +33,9 @@ struct AttnArgs {
   void* O;
   float* lse;  // may be nullptr
   const int* lens;  // dev [B] valid tokens per prompt (clamped to [0, S]), or nullptr for S everywhere
-  int B, S, Hq, Hkv, D;
+  const int* cu;    // packed layout: dev [B + 1] token offsets (prompt b = tokens [cu[b], cu[b+1]) of `total`), else nullptr
+  int total;        // packed layout: tokens in the tensors
+  int B, S, Hq, Hkv, D;   // S: tokens per prompt in memory (padded layout) / longest prompt (packed layout)
   float scale;
 };
 
@@ -57,6 +59,23 @@ hipError_t launch_learn(const void* hn, const void* hs, int n, int Hkv, int D, i
                         float* sigma_out, int* k_out, void* U_packed, int r_pad, void* workspace, hipStream_t s);
 hipError_t launch_head_distance(const void* hp, const void* hm, int n, int Hkv, int D, int dtype, float* D_out,
                                 void* workspace, hipStream_t s);
+
+// Where prompt b starts (in tokens) and how many tokens it has.  Packed layout: read from cu, clamped so that every
+// access derived from them stays inside the tensors whatever cu holds.
+__device__ __forceinline__ void prompt_extent(const AttnArgs& a, int b, size_t& tok0, int& len) {
+  if (a.cu) {
+    const int c0 = min(max(a.cu[b], 0), a.total);
+    tok0 = (size_t)c0;
+    len = min(max(a.cu[b + 1] - c0, 0), min(a.S, a.total - c0));
+  } else {
+    tok0 = (size_t)b * a.S;
+    len = a.lens ? min(max(a.lens[b], 0), a.S) : a.S;
+  }
+}
+// lse[(b, hq, token i of the prompt)]: [B, Hq, S] in the padded layout, [Hq, total] in the packed one
+__device__ __forceinline__ size_t lse_index(const AttnArgs& a, int b, int hq, size_t tok0, int i) {
+  return a.cu ? (size_t)hq * a.total + tok0 + i : ((size_t)b * a.Hq + hq) * a.S + i;
+}
 
 __device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 

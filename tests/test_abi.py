@@ -22,7 +22,8 @@ def test_exports_every_declared_symbol(B):
     assert {"seka_route", "seka_edit_keys", "seka_attention_prefill", "seka_attention_plain",
             "seka_route_workspace_bytes", "seka_status_string", "seka_set_tuning",
             "seka_attention_decode", "seka_decode_workspace_bytes", "seka_attention_prefill_ragged",
-            "seka_learn_workspace_bytes", "seka_learn_projection", "seka_head_distance"} <= names
+            "seka_learn_workspace_bytes", "seka_learn_projection", "seka_head_distance",
+            "seka_attention_prefill_packed"} <= names
     for n in names:
         assert hasattr(B.lib, n), f"libseka.so does not export {n}"
 
@@ -166,3 +167,19 @@ def test_learn_rejects_bad_arguments(B):
     assert hd(w=None) == 8
     assert hd(wb=15) == 8
     assert hd(sh=_shape(B, dtype=7)) == 3
+
+
+def test_packed_rejects_bad_arguments(B):
+    L = B.lib
+    L.seka_attention_prefill_packed.argtypes = [ctypes.c_void_p] * 5 + [ctypes.POINTER(B.seka_shape), ctypes.POINTER(B.seka_steer),
+                                                ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+    ok = _shape(B)
+    big = 1 << 32
+    q, k, v, o, cu = (FAKE + i * big for i in range(5))
+    call = lambda cu=cu, total=300, sh=ok, o=o: L.seka_attention_prefill_packed(q, k, v, o, None, ctypes.byref(sh), None, cu, total, None)
+    assert call(cu=None) == 1
+    assert call(cu=cu + 2) == 4
+    assert call(total=0) == 2
+    assert call(total=1 << 31) == 2
+    assert call(sh=_shape(B, Hq=5)) == 2
+    assert call(o=q) == 5

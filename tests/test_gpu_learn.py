@@ -138,3 +138,41 @@ def test_head_distance_matches_oracle(seka, dtype, B, S, Hkv, D):
     seka.seka_head_distance(H.to_device(hp, dtype).view(B, S, Hkv, D), H.to_device(hp, dtype).view(B, S, Hkv, D), same)
     torch.cuda.synchronize()
     assert torch.all(same == 0)
+
+
+def test_learned_basis_steers_the_prefill(seka):
+    """Offline stage -> inference: the packed basis the GPU learns (per-head rank from the gamma rule, zero-padded
+    to a common width) steers seka_attention_prefill like the basis the oracle learns.  Singular vectors are only
+    fixed up to sign, which the projector U U^T does not see."""
+    import torch
+    print("learn -> prefill", flush=True)
+    n, Hkv, Hq, D, r_pad, gamma = 2048, 2, 8, 128, 32, 0.85
+    ha, hb = inputs.paired_key_samples(n, Hkv, D, seed=12, dtype="bf16", rank=16, decay=0.85)
+    wide = lambda x: inputs.bf16_bits_to_f32(x).astype(np.float64)
+    ref_U, _, ref_k = orc.learn_projection(wide(ha), wide(hb), gamma)
+    U_ref = np.zeros((Hkv, 1, D, r_pad))
+    for h in range(Hkv):
+        assert ref_k[h] <= r_pad
+        U_ref[h, 0, :, :ref_k[h]] = ref_U[h][:, :ref_k[h]]
+    U_ref = wide(inputs.store(U_ref, "bf16"))                        # the basis as a bf16 tensor would hold it
+
+    U = torch.empty((Hkv, D, D), device="cuda")
+    sig = torch.empty((Hkv, D), device="cuda")
+    k = torch.empty((Hkv,), dtype=torch.int32, device="cuda")
+    Up = torch.empty((Hkv, D, r_pad), device="cuda", dtype=torch.bfloat16)
+    seka.seka_learn_projection(H.to_device(ha, "bf16").view(2, n // 2, Hkv, D), H.to_device(hb, "bf16").view(2, n // 2, Hkv, D),
+                               gamma, U, sig, k, U_packed=Up)
+    torch.cuda.synchronize()
+    assert k.cpu().tolist() == [int(x) for x in ref_k]
+
+    inp = inputs.make_layer("learned", "bf16", B=2, S=300, Hq=Hq, Hkv=Hkv, D=D, M=1, r=r_pad, gain=1.5,
+                            mask_recipe=("cover", 0.25, 0.25, 3), seed=31)
+    o = H.oracle_inputs(inp)
+    dev = H.DeviceInputs(inp)
+    O = torch.empty_like(dev.Q)
+    seka.seka_attention_prefill(dev.Q, dev.K, dev.V, O, Up.view(Hkv, 1, D, r_pad), dev.gain, dev.mask, scale=inp.scale)
+    torch.cuda.synchronize()
+    ref_O, _ = orc.steered_attention(o["Q"], o["K"], o["V"], U_ref, inp.gain, inp.mask, scale=inp.scale)
+    plain_O, _ = orc.causal_attention(o["Q"], o["K"], o["V"], scale=inp.scale)
+    assert np.abs(ref_O - plain_O).max() > 1e-2, "steering with the learned basis has no visible effect: vacuous"
+    H.assert_close_bf16(H.to_f64(O), ref_O, "prefill steered with the learned basis")

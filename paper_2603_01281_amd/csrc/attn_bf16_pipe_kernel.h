@@ -813,7 +813,6 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     // into that step, away from the MFMAs it is meant to share the issue port with.
 #pragma unroll
     for (int rp = 0; rp < RPW; ++rp) asm volatile("" : "+v"(pn[rp][0]), "+v"(pn[rp][1]), "+v"(l_run[rp]));
-    asm volatile("" : "+v"(kpre[0]), "+v"(kpre[1]));
     __builtin_amdgcn_sched_barrier(0);
     rescale_outputs();
 #pragma unroll

@@ -121,10 +121,13 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   // nQB - 1 - p and block p.  Every workgroup then scans nQB + 1 key tiles (no imbalance from causality), the
   // steering set-up is done once for both, and the first loads of the second block overlap the first block's
   // output stores.  (With nQB odd the middle block is on its own.)
-  const int per_qb = nHC * a.B;
-  const int pair = (int)(blockIdx.x / per_qb);
-  const int rem = blockIdx.x % per_qb;
-  const int b = rem / nHC, hc = rem % nHC;
+  // blockIdx = (prompt, pair, head chunk), head chunk fastest: workgroups are dispatched round-robin over the
+  // XCDs in index order, so with 8 head chunks an XCD's L2 serves one KV head, and the workgroups resident at the
+  // same time walk the K / V tiles of the same prompt from tile 0 on, at the same pace.
+  const int npairs = (nQB + 1) / 2;
+  const int hc = (int)(blockIdx.x % nHC);
+  const int bp = (int)(blockIdx.x / nHC);
+  const int b = bp / npairs, pair = bp % npairs;
   const int hq0 = hc * HPW;
   const int h = hq0 / G;
   size_t tok0;                               // first token of this prompt in the tensors

@@ -101,6 +101,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   unsigned char* Vst = smem + DMA_STAGES * TB;                   // [3][16 KB] swizzled V tiles
   constexpr int Rpad = 32 * NKR;
   constexpr bool DENSE = NKR >= 2;         // edit with the dense matrix g P (see attention_bf16_pipe_smem_bytes)
+  constexpr bool kEventsInHot = STEER && !DENSE;   // steering events handled inside the hot loop (see the tile loop)
   uint16_t* UN = reinterpret_cast<uint16_t*>(smem + 2 * DMA_STAGES * TB);
   uint16_t* U1 = UN;                       // low rank: operand (rb, s) of U_cat^T K^T: [2][4][64 lanes][8]
   uint16_t* U2 = UN + D * Rpad;            // low rank: operand (s, half) of U_cat Z: [4][2][64 lanes][8]
@@ -699,7 +700,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
       issue_v(t + 2);                                       // its first block belongs to tile t + 1
     }
   };
-  auto bottom = [&](auto sure_c, int t) __attribute__((always_inline)) {
+  auto bottom = [&](auto sure_c, auto events_c, int t) __attribute__((always_inline)) {
 #ifdef SEKA_CYCLE_PROBE
     const unsigned long long w0 = __builtin_amdgcn_s_memtime();
 #endif
@@ -714,7 +715,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 #else
     dma_barrier();
 #endif
-    if (STEER) {
+    if (STEER && decltype(events_c)::value) {
       // one scalar compare in the common case; tiles past the end and unsteered heads have no bit set
       const int tn = t + 2;
       if (__builtin_expect(tn == tile_evt, 0)) {
@@ -836,22 +837,38 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     top(std::true_type{}, st_c, t);
     step(integral_constant<int, ST * TB + HB>{}, integral_constant<int, ((ST + 1) % 3) * TB>{}, integral_constant<int, ((2 * ST + 5) % 6) * HB>{}, sc0, sc1, pb, kpre);
     step(integral_constant<int, ((ST + 1) % 3) * TB>{}, integral_constant<int, ((ST + 1) % 3) * TB + HB>{}, integral_constant<int, 2 * ST * HB>{}, sc1, sc0, pb, kpre);
-    bottom(std::true_type{}, t);
+    bottom(std::true_type{}, std::integral_constant<bool, kEventsInHot>{}, t);
   };
 
-  // Hot iterations: tile t is seen in full by every row of this wave, and tile t + 2 exists and is complete.
+  // Hot iterations: tile t is seen in full by every row of this wave and tile t + 2 exists and is complete.  They
+  // run in whole turns of the ring with a single loop exit (exits after every tile made the compiler park what
+  // the code after the loop needs in scratch memory, inside the loop).  Everything else before the wave's last
+  // tile runs the same pipelined step with run-time ring offsets and guarded loads (a slower tile).
+  // Steering events (a tile to edit, a summary word to reload): the edit code being reachable from the hot loop
+  // makes every iteration slower, even when it never runs (registers the edit needs stay live across the loop and
+  // the compiler shortens the distance between LDS reads and MFMAs: 9 % in cycles).  With the dense edit it pays
+  // to keep the events out of the hot loop and take the slower tile for them (cfg4, cfg5: 4 % faster); with the
+  // low-rank edit it does not (cfg3: 2 % slower), so there the hot loop handles them.
   const int t_hot = min(tw_last, min(ntiles, S / BK) - 2);
   int t = 0;
-  {
-    using std::integral_constant;
-    // whole turns of the ring only: a single loop exit (exits after every tile made the compiler park the values
-    // the code after the loop needs in scratch memory, inside the loop); the remainder runs below
 #pragma nounroll
-    for (; t + 3 <= t_hot; t += 3) {
-      hot(integral_constant<int, 0>{}, t);
-      hot(integral_constant<int, 1>{}, t + 1);
-      hot(integral_constant<int, 2>{}, t + 2);
+  while (t < tw_last) {
+    if (t % 3 == 0) {
+      using std::integral_constant;
+#pragma nounroll
+      for (; t + 3 <= t_hot && (!STEER || kEventsInHot || tile_evt > t + 4); t += 3) {
+        hot(integral_constant<int, 0>{}, t);
+        hot(integral_constant<int, 1>{}, t + 1);
+        hot(integral_constant<int, 2>{}, t + 2);
+      }
+      if (t >= tw_last) break;
     }
+    top(std::false_type{}, IC0{}, t);
+    const int off = (t % 3) * TB, offn = ((t + 1) % 3) * TB;
+    step(off + HB, offn, (int)vpos(2 * t - 1), sc0, sc1, pb, kpre);
+    step(offn, offn + HB, (int)vpos(2 * t), sc1, sc0, pb, kpre);
+    bottom(std::false_type{}, std::true_type{}, t);
+    ++t;
   }
 #ifdef SEKA_CYCLE_PROBE
   const unsigned long long prb_tail = __builtin_amdgcn_s_memtime();
@@ -863,7 +880,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     const int off = (t % 3) * TB, offn = ((t + 1) % 3) * TB;
     step(off + HB, offn, (int)vpos(2 * t - 1), sc0, sc1, pb, kpre);
     step(offn, offn + HB, (int)vpos(2 * t), sc1, sc0, pb, kpre);
-    bottom(std::false_type{}, t);
+    bottom(std::false_type{}, std::true_type{}, t);
   }
   // ---- the wave's last tile (causal mask, nothing further to score), then idle turns while other waves finish.
   // The second block of that tile may still be in flight during its own iteration (V runs half a tile behind), so
@@ -903,7 +920,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
       owed = true;
       owed_off = (int)vpos(2 * t + 1);
     }
-    bottom(std::false_type{}, t);
+    bottom(std::false_type{}, std::true_type{}, t);
   }
   if (owed) pv_half(owed_off, pb);
 

@@ -24,7 +24,7 @@
 // The softmax runs per 32-key block (half a tile), which halves the score registers the pipeline needs.
 // K tiles live in a ring of three LDS stages; V in a ring of six half tiles that runs half a tile behind K
 // (see the tile loads).  K(t+2) and the V blocks 2t+3, 2t+4 are requested at the top of iteration t and K(t+2)
-// is edited (highlighted keys only) at the bottom of iteration t.
+// is edited (highlighted keys only) between the two steps of iteration t + 1.
 #pragma once
 #include <type_traits>
 #ifndef SEKA_B_SCHED
@@ -687,7 +687,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   for (int i = 0; i < 2; ++i) kpre[i] = *(pipe_lds_bf16x8_ptr)(uintptr_t)(kaddr[i] + HB);
 
   // Top of iteration t: request K(t+2), then the V blocks 2t+3 and 2t+4.  Bottom: everything but those two V
-  // blocks must have landed before the next iteration; then edit K(t+2) if it holds highlighted keys.
+  // blocks must have landed before the next iteration (K(t+2) is edited there, see `events`).
   // The hot loop only runs where tile t + 2 exists and is complete (`sure`): no tests there.
   auto top = [&](auto sure_c, auto stage_c, int t) __attribute__((always_inline)) {
     constexpr bool SURE = decltype(sure_c)::value;
@@ -700,7 +700,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
       issue_v(t + 2);                                       // its first block belongs to tile t + 1
     }
   };
-  auto bottom = [&](auto sure_c, auto events_c, int t) __attribute__((always_inline)) {
+  auto bottom = [&](auto sure_c, int t) __attribute__((always_inline)) {
 #ifdef SEKA_CYCLE_PROBE
     const unsigned long long w0 = __builtin_amdgcn_s_memtime();
 #endif
@@ -715,24 +715,33 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 #else
     dma_barrier();
 #endif
-    if (STEER && decltype(events_c)::value) {
-      // one scalar compare in the common case; tiles past the end and unsteered heads have no bit set
-      const int tn = t + 2;
-      if (__builtin_expect(tn == tile_evt, 0)) {
-        const unsigned sh = tn & 63;
-        if (sh == 0u) anyw = any_word(tn);
-        tile_evt = next_event(tn);
-        if ((anyw >> sh) & 1ull) {
+  };
+
+  // Steering events of the tile that landed at the bottom of the previous iteration (tile t + 1 in iteration t):
+  // handled between the two steps of an iteration, where a basic-block boundary exists anyway (the conditional
+  // rescale).  Directly after the per-tile barrier the same branch kept the compiler from moving the next step's
+  // first LDS reads up, which cost every iteration of the steered kernels 7-9 % even with nothing to edit.  The
+  // second step is the first reader of that tile; its two prefetched fragments are read again after an edit.
+  auto events = [&](int t, int knext_off, bf16x8 (&kp)[2]) __attribute__((always_inline)) {
+    if (!STEER) return;
+    // one scalar compare in the common case; tiles past the end and unsteered heads have no bit set
+    const int tn = t + 1;
+    if (__builtin_expect(tn == tile_evt, 0)) {
+      const unsigned sh = tn & 63;
+      if (sh == 0u) anyw = any_word(tn);
+      tile_evt = next_event(tn);
+      if ((anyw >> sh) & 1ull) {
 #ifdef SEKA_CYCLE_PROBE
-          const unsigned long long c0 = __builtin_amdgcn_s_memtime();
+        const unsigned long long c0 = __builtin_amdgcn_s_memtime();
 #endif
-          edit_tile(Kst + (tn % 3) * TB, hlbits[tn]);
-          dma_barrier();
+        edit_tile(Kst + (tn % 3) * TB, hlbits[tn]);
+        dma_barrier();
+#pragma unroll
+        for (int i = 0; i < 2; ++i) kp[i] = *(pipe_lds_bf16x8_ptr)(uintptr_t)(kaddr[i] + knext_off);
 #ifdef SEKA_CYCLE_PROBE
-          prb_edit += __builtin_amdgcn_s_memtime() - c0;
-          prb_n += 1;
+        prb_edit += __builtin_amdgcn_s_memtime() - c0;
+        prb_n += 1;
 #endif
-        }
       }
     }
   };
@@ -836,8 +845,9 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     for (int db = 0; db < DB; ++db) asm volatile("" : "+v"(vaddr[db]));
     top(std::true_type{}, st_c, t);
     step(integral_constant<int, ST * TB + HB>{}, integral_constant<int, ((ST + 1) % 3) * TB>{}, integral_constant<int, ((2 * ST + 5) % 6) * HB>{}, sc0, sc1, pb, kpre);
+    if (kEventsInHot) events(t, ((ST + 1) % 3) * TB, kpre);
     step(integral_constant<int, ((ST + 1) % 3) * TB>{}, integral_constant<int, ((ST + 1) % 3) * TB + HB>{}, integral_constant<int, 2 * ST * HB>{}, sc1, sc0, pb, kpre);
-    bottom(std::true_type{}, std::integral_constant<bool, kEventsInHot>{}, t);
+    bottom(std::true_type{}, t);
   };
 
   // Hot iterations: tile t is seen in full by every row of this wave and tile t + 2 exists and is complete.  They
@@ -856,7 +866,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     if (t % 3 == 0) {
       using std::integral_constant;
 #pragma nounroll
-      for (; t + 3 <= t_hot && (!STEER || kEventsInHot || tile_evt > t + 4); t += 3) {
+      for (; t + 3 <= t_hot && (!STEER || kEventsInHot || tile_evt > t + 3); t += 3) {
         hot(integral_constant<int, 0>{}, t);
         hot(integral_constant<int, 1>{}, t + 1);
         hot(integral_constant<int, 2>{}, t + 2);
@@ -866,8 +876,9 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     top(std::false_type{}, IC0{}, t);
     const int off = (t % 3) * TB, offn = ((t + 1) % 3) * TB;
     step(off + HB, offn, (int)vpos(2 * t - 1), sc0, sc1, pb, kpre);
+    events(t, offn, kpre);
     step(offn, offn + HB, (int)vpos(2 * t), sc1, sc0, pb, kpre);
-    bottom(std::false_type{}, std::true_type{}, t);
+    bottom(std::false_type{}, t);
     ++t;
   }
 #ifdef SEKA_CYCLE_PROBE
@@ -879,8 +890,9 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     top(std::false_type{}, IC0{}, t);
     const int off = (t % 3) * TB, offn = ((t + 1) % 3) * TB;
     step(off + HB, offn, (int)vpos(2 * t - 1), sc0, sc1, pb, kpre);
+    events(t, offn, kpre);
     step(offn, offn + HB, (int)vpos(2 * t), sc1, sc0, pb, kpre);
-    bottom(std::false_type{}, std::true_type{}, t);
+    bottom(std::false_type{}, t);
   }
   // ---- the wave's last tile (causal mask, nothing further to score), then idle turns while other waves finish.
   // The second block of that tile may still be in flight during its own iteration (V runs half a tile behind), so
@@ -890,6 +902,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 #pragma nounroll
   for (; t < ntiles; ++t) {
     top(std::false_type{}, IC0{}, t);
+    events(t, 0, kpre);                     // this wave scores nothing further; other waves may (kpre is dead here)
     if (owed) {
       pv_half(owed_off, pb);
       owed = false;
@@ -920,7 +933,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
       owed = true;
       owed_off = (int)vpos(2 * t + 1);
     }
-    bottom(std::false_type{}, std::true_type{}, t);
+    bottom(std::false_type{}, t);
   }
   if (owed) pv_half(owed_off, pb);
 

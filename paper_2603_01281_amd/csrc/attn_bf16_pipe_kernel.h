@@ -101,7 +101,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   unsigned char* Vst = smem + DMA_STAGES * TB;                   // [3][16 KB] swizzled V tiles
   constexpr int Rpad = 32 * NKR;
   constexpr bool DENSE = NKR >= 2;         // edit with the dense matrix g P (see attention_bf16_pipe_smem_bytes)
-  constexpr bool kEventsInHot = STEER && !DENSE;   // steering events handled inside the hot loop (see the tile loop)
+  constexpr bool kEventsInHot = STEER && (!DENSE || NW == 8);   // steering events handled inside the hot loop (see the tile loop)
   uint16_t* UN = reinterpret_cast<uint16_t*>(smem + 2 * DMA_STAGES * TB);
   uint16_t* U1 = UN;                       // low rank: operand (rb, s) of U_cat^T K^T: [2][4][64 lanes][8]
   uint16_t* U2 = UN + D * Rpad;            // low rank: operand (s, half) of U_cat Z: [4][2][64 lanes][8]
@@ -854,11 +854,9 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   // run in whole turns of the ring with a single loop exit (exits after every tile made the compiler park what
   // the code after the loop needs in scratch memory, inside the loop).  Everything else before the wave's last
   // tile runs the same pipelined step with run-time ring offsets and guarded loads (a slower tile).
-  // Steering events (a tile to edit, a summary word to reload): the edit code being reachable from the hot loop
-  // makes every iteration slower, even when it never runs (registers the edit needs stay live across the loop and
-  // the compiler shortens the distance between LDS reads and MFMAs: 9 % in cycles).  With the dense edit it pays
-  // to keep the events out of the hot loop and take the slower tile for them (cfg4, cfg5: 4 % faster); with the
-  // low-rank edit it does not (cfg3: 2 % slower), so there the hot loop handles them.
+  // Steering events (a tile to edit, a summary word to reload) are handled inside the hot loop, except in the
+  // one shape where that measured slower than leaving the loop for the slower tile: the dense edit with seven
+  // waves (cfg5: 3 % faster outside; cfg4, dense with eight waves: 3 % faster inside).
   const int t_hot = min(tw_last, min(ntiles, S / BK) - 2);
   int t = 0;
 #pragma nounroll

@@ -27,7 +27,7 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
 # --pmc WRITE_SIZE runs of this script, each scaled by what the same counter reads for a 256 MiB device copy:
 # x2.0 for FETCH_SIZE, x1.0 for WRITE_SIZE; summary in profiles/attention_bf16_cfg3_hbm_traffic.md).
 # Algorithmic bytes are Q + K + V + O = 671 MB; the rest is K/V re-fetched by workgroups on different XCDs.
-MEASURED_TRAFFIC_BYTES = {"fetch": 288048.5 * 1024 * 2.0, "write": 262144.2 * 1024 * 1.0}
+MEASURED_TRAFFIC_BYTES = {"fetch": 289345.6 * 1024 * 2.0, "write": 262144.0 * 1024 * 1.0}
 
 
 def parse():

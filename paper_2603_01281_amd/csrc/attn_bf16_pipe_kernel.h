@@ -843,8 +843,8 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(kaddr[ks]));
 #pragma unroll
     for (int db = 0; db < DB; ++db) asm volatile("" : "+v"(vaddr[db]));
-    top(std::true_type{}, st_c, t);
     step(integral_constant<int, ST * TB + HB>{}, integral_constant<int, ((ST + 1) % 3) * TB>{}, integral_constant<int, ((2 * ST + 5) % 6) * HB>{}, sc0, sc1, pb, kpre);
+    top(std::true_type{}, st_c, t);
     if (kEventsInHot) events(t, ((ST + 1) % 3) * TB, kpre);
     step(integral_constant<int, ((ST + 1) % 3) * TB>{}, integral_constant<int, ((ST + 1) % 3) * TB + HB>{}, integral_constant<int, 2 * ST * HB>{}, sc1, sc0, pb, kpre);
     bottom(std::true_type{}, t);

@@ -23,8 +23,9 @@
 //     earlier), so the exponentials are spread over twelve MFMAs instead of four.
 // The softmax runs per 32-key block (half a tile), which halves the score registers the pipeline needs.
 // K tiles live in a ring of three LDS stages; V in a ring of six half tiles that runs half a tile behind K
-// (see the tile loads).  K(t+2) and the V blocks 2t+3, 2t+4 are requested at the top of iteration t and K(t+2)
-// is edited (highlighted keys only) between the two steps of iteration t + 1.
+// (see the tile loads).  K(t+2) and the V blocks 2t+3, 2t+4 are requested during iteration t (in the hot loop
+// between its two steps, so that the first step's LDS reads follow the per-tile barrier directly) and K(t+2) is
+// edited (highlighted keys only) between the two steps of iteration t + 1.
 #pragma once
 #include <type_traits>
 #ifndef SEKA_B_SCHED
@@ -686,8 +687,10 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 #pragma unroll
   for (int i = 0; i < 2; ++i) kpre[i] = *(pipe_lds_bf16x8_ptr)(uintptr_t)(kaddr[i] + HB);
 
-  // Top of iteration t: request K(t+2), then the V blocks 2t+3 and 2t+4.  Bottom: everything but those two V
-  // blocks must have landed before the next iteration (K(t+2) is edited there, see `events`).
+  // `top` of iteration t: request K(t+2), then the V blocks 2t+3 and 2t+4; their ring slots are free since the
+  // barrier of iteration t - 1.  Bottom: everything but those two V blocks must have landed before the next
+  // iteration (K(t+2) is edited there, see `events`).  The hot loop calls `top` between its two steps: requests
+  // issued right after the barrier delayed the first step's operand reads (1-2 % of the kernel).
   // The hot loop only runs where tile t + 2 exists and is complete (`sure`): no tests there.
   auto top = [&](auto sure_c, auto stage_c, int t) __attribute__((always_inline)) {
     constexpr bool SURE = decltype(sure_c)::value;

@@ -141,6 +141,13 @@ def time_config(torch, seka, inputs, cfg, iters=10):
     edit_ms = event_time(torch, lambda: seka.seka_edit_keys(K, K2, U, gain, mask, w=w), iters, warm=10)
     out["edit_keys_ms"] = round(edit_ms, 4)
     out["edit_keys_GBps"] = round(2 * K.numel() * 2 / edit_ms / 1e6, 1)
+    # the unfused alternative for callers that keep K' anyway (a KV cache): edit once, then unsteered attention on K'
+    def run_two_pass():
+        seka.seka_edit_keys(K, K2, U, gain, mask, w=w)
+        seka.seka_attention_plain(Q, K2, V, O)
+    plain2, two_pass = paired_medians(torch, run_plain, run_two_pass, fl)
+    out["edit_then_plain_ms"] = round(two_pass, 4)
+    out["edit_then_plain_overhead_pct"] = round(100 * (two_pass / plain2 - 1), 2)
     # generation step over the (edited) cache: reads K and V once
     qd = Q[:, -1].contiguous()
     Od = torch.empty_like(qd)

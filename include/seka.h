@@ -100,6 +100,27 @@ seka_status seka_route(const void* Q, const seka_shape* sh, const float* proto, 
                        void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /*
+ * seka_route_ragged — seka_route for a batch whose prompts differ in length (paper Sec. 3.3: the query that
+ * routes is taken at the end of each prompt, so its position differs per prompt).  For prompt b the mean runs
+ * over its last `window` tokens, t in [max(0, len_b - window), len_b): window = 1 is the paper's last prompt
+ * token, window >= S the whole prompt.  Everything else is seka_route.
+ *
+ * cu_seqlens == NULL: Q dev [B,S,Hq,D] (padded); len_b = seq_lens[b], seq_lens dev [B] int32 (required).
+ * cu_seqlens != NULL: Q dev [total_tokens,Hq,D] (packed); cu_seqlens dev [B+1] int32, ascending, cu[0] = 0,
+ *                     cu[B] = total_tokens; prompt b is rows cu[b] .. cu[b+1]-1; seq_lens is ignored and
+ *                     sh->S is the longest prompt.  Rows are clamped to the tensor on the device.
+ * len_b is clamped to [0, S].  A prompt without tokens has q_bar = 0: SOFTMAX_COS gives 1/M for every expert,
+ * PAPER_EQ6 gives 0.
+ * workspace  dev scratch of at least seka_route_ragged_workspace_bytes(sh, window) bytes, 16-byte aligned.
+ * Errors as seka_route; both length arrays NULL is SEKA_ERR_NULL, window < 1 SEKA_ERR_SHAPE.
+ */
+size_t seka_route_ragged_workspace_bytes(const seka_shape* sh, int32_t window);
+seka_status seka_route_ragged(const void* Q, const seka_shape* sh, const float* proto, int32_t M,
+                              const int32_t* seq_lens, const int32_t* cu_seqlens, int64_t total_tokens,
+                              int32_t window, int32_t mode, float tau, float* w_out, void* workspace,
+                              size_t workspace_bytes, void* hip_stream);
+
+/*
  * seka_edit_keys — the standalone key-editing hook (Algorithm 1 / 2, inference part):
  *   K_out[b,t,h,:] = K_in[b,t,h,:] + gain[h] * sum_m w[b,h,m] U[h,m] (U[h,m]^T K_in[b,t,h,:])
  * where mask[b,t] != 0 and gain[h] != 0; K_out = K_in elsewhere.

@@ -51,6 +51,10 @@ lib.seka_route_workspace_bytes.restype = _sz
 lib.seka_route_workspace_bytes.argtypes = [_shape_p, _i32, _i32]
 lib.seka_route.restype = _i32
 lib.seka_route.argtypes = [_vp, _shape_p, _vp, _i32, _i32, _i32, _i32, _f32, _vp, _vp, _sz, _vp]
+lib.seka_route_ragged_workspace_bytes.restype = _sz
+lib.seka_route_ragged_workspace_bytes.argtypes = [_shape_p, _i32]
+lib.seka_route_ragged.restype = _i32
+lib.seka_route_ragged.argtypes = [_vp, _shape_p, _vp, _i32, _vp, _vp, ctypes.c_int64, _i32, _i32, _f32, _vp, _vp, _sz, _vp]
 lib.seka_edit_keys.restype = _i32
 lib.seka_edit_keys.argtypes = [_vp, _vp, _shape_p, _steer_p, _vp]
 lib.seka_attention_prefill.restype = _i32
@@ -153,6 +157,31 @@ def seka_route(Q, proto, t0, t1, mode=SEKA_ROUTE_SOFTMAX_COS, tau=10.0, w_out=No
     _check(lib.seka_route(_dev(Q, "Q"), ctypes.byref(sh), _dev(proto, "proto"), M, t0, t1, mode, float(tau),
                           _dev(w_out, "w_out"), _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
                           _stream(stream)))
+    return w_out
+
+
+def seka_route_ragged(Q, proto, window, seq_lens=None, cu_seqlens=None, max_len=None, mode=SEKA_ROUTE_SOFTMAX_COS,
+                      tau=10.0, w_out=None, workspace=None, stream=None):
+    """Per-prompt routing over the last `window` tokens of each prompt.  Padded: Q [B,S,Hq,D] with seq_lens [B]
+    int32 device tensor.  Packed: Q [total,Hq,D] with cu_seqlens [B+1] int32 device tensor and max_len."""
+    torch = _torch()
+    Hkv, M, _ = proto.shape
+    if cu_seqlens is not None:
+        total, Hq, D = Q.shape
+        B, S = cu_seqlens.numel() - 1, int(max_len)
+    else:
+        B, S, Hq, D = Q.shape
+        total = 0
+    sh = _shape(B, S, Hq, Hkv, D, _dtype_code(Q), 0.0)
+    if w_out is None:
+        w_out = torch.empty((B, Hkv, M), dtype=torch.float32, device=Q.device)
+    need = lib.seka_route_ragged_workspace_bytes(ctypes.byref(sh), window)
+    if workspace is None:
+        workspace = torch.empty(max(need, 16), dtype=torch.uint8, device=Q.device)
+    _check(lib.seka_route_ragged(_dev(Q, "Q"), ctypes.byref(sh), _dev(proto, "proto"), M, _dev(seq_lens, "seq_lens"),
+                                 _dev(cu_seqlens, "cu_seqlens"), total, window, mode, float(tau), _dev(w_out, "w_out"),
+                                 _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
+                                 _stream(stream)))
     return w_out
 
 

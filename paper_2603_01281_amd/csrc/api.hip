@@ -160,6 +160,36 @@ seka_status seka_route(const void* Q, const seka_shape* sh, const float* proto, 
   return launch_status(e);
 }
 
+size_t seka_route_ragged_workspace_bytes(const seka_shape* sh, int32_t window) {
+  if (check_shape(sh, true) != SEKA_OK || window < 1) return 0;
+  return seka::route_workspace_bytes(sh->B, sh->Hkv, sh->D, 0, window < sh->S ? window : sh->S);
+}
+
+seka_status seka_route_ragged(const void* Q, const seka_shape* sh, const float* proto, int32_t M,
+                              const int32_t* seq_lens, const int32_t* cu_seqlens, int64_t total_tokens,
+                              int32_t window, int32_t mode, float tau, float* w_out, void* workspace,
+                              size_t workspace_bytes, void* hip_stream) {
+  seka_status rc = check_shape(sh, true);
+  if (rc != SEKA_OK) return rc;
+  if (!Q || !proto || !w_out) return SEKA_ERR_NULL;
+  if (!seq_lens && !cu_seqlens) return SEKA_ERR_NULL;
+  if (M < 1 || M > SEKA_MAX_EXPERTS || window < 1) return SEKA_ERR_SHAPE;
+  if (cu_seqlens && (total_tokens < 1 || total_tokens > 0x7fffffffLL)) return SEKA_ERR_SHAPE;
+  if (mode != SEKA_ROUTE_SOFTMAX_COS && mode != SEKA_ROUTE_PAPER_EQ6) return SEKA_ERR_UNSUPPORTED;
+  if (!std::isfinite(tau)) return SEKA_ERR_SHAPE;
+  if (misaligned(Q) || misaligned(proto) || (reinterpret_cast<uintptr_t>(w_out) & 3u)) return SEKA_ERR_ALIGN;
+  if ((reinterpret_cast<uintptr_t>(seq_lens) & 3u) || (reinterpret_cast<uintptr_t>(cu_seqlens) & 3u)) return SEKA_ERR_ALIGN;
+  const int win = window < sh->S ? window : sh->S;
+  const size_t need = seka::route_workspace_bytes(sh->B, sh->Hkv, sh->D, 0, win);
+  if (!workspace || workspace_bytes < need) return SEKA_ERR_WORKSPACE;
+  if (misaligned(workspace)) return SEKA_ERR_ALIGN;
+  (void)hipGetLastError();
+  hipError_t e = seka::launch_route(Q, sh->B, sh->S, sh->Hq, sh->Hkv, sh->D, sh->dtype, proto, M, 0, win, mode, tau,
+                                    w_out, workspace, reinterpret_cast<hipStream_t>(hip_stream),
+                                    cu_seqlens ? nullptr : seq_lens, cu_seqlens, cu_seqlens ? (int)total_tokens : 0, win);
+  return launch_status(e);
+}
+
 seka_status seka_edit_keys(const void* K_in, void* K_out, const seka_shape* sh, const seka_steer* st,
                            void* hip_stream) {
   seka_status rc = check_shape(sh, false);

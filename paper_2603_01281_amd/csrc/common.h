@@ -48,7 +48,8 @@ hipError_t launch_edit_keys(const void* K_in, void* K_out, int B, int S, int Hkv
 size_t route_workspace_bytes(int B, int Hkv, int D, int t0, int t1);
 hipError_t launch_route(const void* Q, int B, int S, int Hq, int Hkv, int D, int dtype, const float* proto,
                         int M, int t0, int t1, int mode, float tau, float* w_out, void* workspace,
-                        hipStream_t s);
+                        hipStream_t s, const int* lens = nullptr, const int* cu = nullptr, int total = 0,
+                        int window = 0);
 
 size_t decode_workspace_bytes(int B, int S, int Hq, int Hkv, int D);
 hipError_t launch_decode(const void* q, const void* K, const void* V, void* O, float* lse, const int* lens, int B, int S,

@@ -51,6 +51,8 @@ template <> struct Vec16<uint16_t> {
 template <typename T, int D>
 __global__ __launch_bounds__(kRouteThreads) void route_partial_kernel(const T* __restrict__ Q, int S, int Hq, int Hkv,
                                                                        int t0, int t1, int chunks,
+                                                                       const int* __restrict__ lens,
+                                                                       const int* __restrict__ cu, int total, int window,
                                                                        float* __restrict__ workspace) {
   constexpr int VE = Vec16<T>::N;
   constexpr int VPR = D / VE;                    // 16-byte vectors per (token, head) row
@@ -59,6 +61,20 @@ __global__ __launch_bounds__(kRouteThreads) void route_partial_kernel(const T* _
   const int G = Hq / Hkv;
   const int bh = blockIdx.y, b = bh / Hkv, h = bh % Hkv;
   const int c = blockIdx.x;
+  size_t row_base = (size_t)b * S;               // first token row of the prompt
+  if (lens != nullptr || cu != nullptr) {        // per-prompt range: the last `window` tokens of the prompt
+    int len;
+    if (cu != nullptr) {
+      const int start = min(max(cu[b], 0), total);
+      len = min(cu[b + 1] - start, total - start);
+      row_base = (size_t)start;
+    } else {
+      len = lens[b];
+    }
+    len = min(max(len, 0), S);
+    t1 = len;
+    t0 = max(0, len - window);
+  }
   const int T_total = t1 - t0;
   const int per = (T_total + chunks - 1) / chunks;
   const int ta = t0 + c * per;
@@ -76,7 +92,7 @@ __global__ __launch_bounds__(kRouteThreads) void route_partial_kernel(const T* _
       const int row = row0 + u * RPP;
       if (row < nrows) {
         const int t = ta + row / G, g = row % G;
-        Vec16<T>::load(Q + (((size_t)b * S + t) * Hq + (size_t)h * G + g) * D + col * VE, v[u]);
+        Vec16<T>::load(Q + ((row_base + t) * Hq + (size_t)h * G + g) * D + col * VE, v[u]);
       } else {
 #pragma unroll
         for (int i = 0; i < VE; ++i) v[u][i] = 0.f;
@@ -103,13 +119,27 @@ __global__ __launch_bounds__(kRouteThreads) void route_partial_kernel(const T* _
 template <int D>
 __global__ __launch_bounds__(kFinishThreads) void route_finish_kernel(const float* __restrict__ workspace, int chunks, float inv_count,
                                                            const float* __restrict__ proto, int Hkv, int M, int mode,
-                                                           float tau, float* __restrict__ w_out) {
+                                                           float tau, const int* __restrict__ lens, const int* __restrict__ cu,
+                                                           int total, int S, int window, int G, float* __restrict__ w_out) {
   __shared__ float qbar[D];
   __shared__ float dots[SEKA_MAX_EXPERTS];
   __shared__ float pnorm2[SEKA_MAX_EXPERTS];
   constexpr int NJ = kFinishThreads / D;
   __shared__ float part[NJ][D];
   const int bh = blockIdx.x, h = bh % Hkv;
+  if (lens != nullptr || cu != nullptr) {        // tokens this prompt contributed (the partial kernel's range)
+    const int b = bh / Hkv;
+    int len;
+    if (cu != nullptr) {
+      const int start = min(max(cu[b], 0), total);
+      len = min(cu[b + 1] - start, total - start);
+    } else {
+      len = lens[b];
+    }
+    len = min(max(len, 0), S);
+    const int count = (len - max(0, len - window)) * G;
+    inv_count = count > 0 ? 1.0f / (float)count : 0.f;
+  }
   {
     const int d = threadIdx.x % D, j = threadIdx.x / D;
     float s = 0.f;
@@ -170,7 +200,10 @@ size_t route_workspace_bytes(int B, int Hkv, int D, int t0, int t1) {
 }
 
 hipError_t launch_route(const void* Q, int B, int S, int Hq, int Hkv, int D, int dtype, const float* proto, int M,
-                        int t0, int t1, int mode, float tau, float* w_out, void* workspace, hipStream_t s) {
+                        int t0, int t1, int mode, float tau, float* w_out, void* workspace, hipStream_t s,
+                        const int* lens, const int* cu, int total, int window) {
+  const bool ragged = lens != nullptr || cu != nullptr;
+  if (ragged) { t0 = 0; t1 = window < S ? window : S; }      // the longest range a prompt can have
   const int chunks = route_chunks(t1 - t0, B * Hkv);
   const dim3 grid(chunks, B * Hkv);
   float* ws = static_cast<float*>(workspace);
@@ -178,9 +211,9 @@ hipError_t launch_route(const void* Q, int B, int S, int Hq, int Hkv, int D, int
 #define SEKA_ROUTE_CASE(T, DD)                                                                                       \
   do {                                                                                                               \
     hipLaunchKernelGGL((route_partial_kernel<T, DD>), grid, dim3(kRouteThreads), 0, s, static_cast<const T*>(Q), S,  \
-                       Hq, Hkv, t0, t1, chunks, ws);                                                                 \
+                       Hq, Hkv, t0, t1, chunks, lens, cu, total, window, ws);                                        \
     hipLaunchKernelGGL((route_finish_kernel<DD>), dim3(B * Hkv), dim3(kFinishThreads), 0, s, ws, chunks, inv_count, proto, Hkv, \
-                       M, mode, tau, w_out);                                                                         \
+                       M, mode, tau, lens, cu, total, S, window, Hq / Hkv, w_out);                                   \
   } while (0)
   if (dtype == SEKA_BF16) {
     if (D == 128) SEKA_ROUTE_CASE(uint16_t, 128); else SEKA_ROUTE_CASE(uint16_t, 64);

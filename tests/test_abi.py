@@ -23,7 +23,7 @@ def test_exports_every_declared_symbol(B):
             "seka_route_workspace_bytes", "seka_status_string", "seka_set_tuning",
             "seka_attention_decode", "seka_decode_workspace_bytes", "seka_attention_prefill_ragged",
             "seka_learn_workspace_bytes", "seka_learn_projection", "seka_head_distance",
-            "seka_attention_prefill_packed"} <= names
+            "seka_attention_prefill_packed", "seka_route_ragged", "seka_route_ragged_workspace_bytes"} <= names
     for n in names:
         assert hasattr(B.lib, n), f"libseka.so does not export {n}"
 
@@ -110,6 +110,27 @@ def test_route_rejects_bad_arguments(B):
     assert call(tau=float("inf")) == 2
     assert call(ws=None) == 8 and call(wsb=need - 1) == 8
     assert call(ws=FAKE * 5 + 8) == 4
+
+
+def test_route_ragged_rejects_bad_arguments(B):
+    L = B.lib
+    ok = _shape(B)
+    need = L.seka_route_ragged_workspace_bytes(ctypes.byref(ok), 1)
+    assert need > 0 and need % 16 == 0
+    assert L.seka_route_ragged_workspace_bytes(ctypes.byref(ok), 0) == 0
+    # a window beyond the prompt needs what the whole prompt needs
+    assert L.seka_route_ragged_workspace_bytes(ctypes.byref(ok), 1 << 30) == L.seka_route_workspace_bytes(ctypes.byref(ok), 0, ok.S)
+    call = lambda **kw: L.seka_route_ragged(kw.get("Q", FAKE), ctypes.byref(kw.get("sh", ok)), kw.get("proto", FAKE * 2), kw.get("M", 4),
+                                            kw.get("lens", FAKE * 7), kw.get("cu", None), kw.get("total", 0), kw.get("window", 1),
+                                            kw.get("mode", 0), kw.get("tau", 10.0), kw.get("w", FAKE * 3), kw.get("ws", FAKE * 5),
+                                            kw.get("wsb", need), None)
+    assert call(Q=None) == 1 and call(w=None) == 1
+    assert call(lens=None) == 1                                   # neither lengths nor offsets
+    assert call(window=0) == 2 and call(M=0) == 2
+    assert call(lens=None, cu=FAKE * 7, total=0) == 2             # packed layout needs its row count
+    assert call(lens=FAKE * 7 + 2) == 4 and call(lens=None, cu=FAKE * 7 + 2, total=10) == 4
+    assert call(mode=9) == 6
+    assert call(ws=None) == 8 and call(wsb=need - 1) == 8
 
 
 def test_tuning_rejects_unknown(B):

@@ -94,3 +94,48 @@ def test_packed_offsets_are_clamped(seka):
     ref_O, _ = orc.causal_attention(o["Q"][:1], o["K"][:1], o["V"][:1], scale=inp.scale)
     H.assert_close_bf16(H.to_f64(O[:200])[None], ref_O, "prompt 0 beside nonsense offsets")
     assert torch.isfinite(O.float()).all()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_route_ragged(seka, dtype):
+    """seka_route_ragged, padded with lengths and packed, against the oracle called prompt by prompt on each
+    prompt's own token range (Sec. 3.3: the routing query sits at the end of each prompt)."""
+    import torch
+    Hq, Hkv, D, M, Ktop = 8, 2, 128, 4, 5
+    lens = [517, 1, 0, 130, 64]
+    B, S = len(lens), max(lens)
+    print(f"route ragged {dtype}", flush=True)
+    Q = inputs.gaussian((B, S, Hq, D), 11, "Q", dtype)
+    Qd = H.to_device(Q, dtype)
+    Q64 = inputs.bf16_bits_to_f32(Q).astype(np.float64) if dtype == "bf16" else Q.astype(np.float64)
+    proto = inputs.unit_prototypes(Hkv, M, D, 11)
+    pd = torch.from_numpy(proto).cuda()
+    g = np.random.default_rng(12)
+    U_top = np.stack([[np.linalg.qr(g.standard_normal((D, Ktop)))[0] for _ in range(M)] for _ in range(Hkv)])
+    sigma = np.sort(g.random((Hkv, M, Ktop)) + 0.1, axis=-1)[..., ::-1].copy()
+    p6 = torch.from_numpy(np.einsum("hmdk,hmk->hmd", U_top, sigma).astype(np.float32)).cuda()
+    lens_dev = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    cu_dev = torch.from_numpy(cu).cuda()
+    extra = 3                                            # rows after the last prompt, never read as a prompt's
+    Qp = torch.cat([Qd[b, :n] for b, n in enumerate(lens)] + [Qd[0, :extra]], dim=0).contiguous()
+    for window in (1, 50, S, 4 * S):
+        ref_w = np.zeros((B, Hkv, M))
+        ref_a = np.zeros((B, Hkv, M))
+        for b, n in enumerate(lens):
+            if n == 0:
+                ref_w[b] = 1.0 / M                       # no query: every cosine is 0
+                continue
+            t0 = max(0, n - window)
+            ref_w[b] = orc.route_softmax_cos(Q64[b:b + 1], proto, t0, n, 10.0)[0]
+            ref_a[b] = orc.route_eq6(Q64[b:b + 1], U_top, sigma, t0, n)[0]
+        for layout in ("padded", "packed"):
+            kw = dict(seq_lens=lens_dev) if layout == "padded" else dict(cu_seqlens=cu_dev, max_len=S)
+            Qin = Qd if layout == "padded" else Qp
+            w = seka.seka_route_ragged(Qin, pd, window, mode=seka.SEKA_ROUTE_SOFTMAX_COS, tau=10.0, **kw)
+            a = seka.seka_route_ragged(Qin, p6, window, mode=seka.SEKA_ROUTE_PAPER_EQ6, tau=0.0, **kw)
+            assert np.abs(H.to_f64(w) - ref_w).max() <= H.ROUTE_ABS, (layout, window)
+            assert np.abs(H.to_f64(a) - ref_a).max() <= H.ROUTE_ABS, (layout, window)
+    # equal lengths and the whole prompt: the same numbers as seka_route
+    full = torch.full((B,), S, dtype=torch.int32, device="cuda")
+    assert torch.equal(seka.seka_route_ragged(Qd, pd, S, seq_lens=full), seka.seka_route(Qd, pd, 0, S))

@@ -28,9 +28,6 @@
 // edited (highlighted keys only) between the two steps of iteration t + 1.
 #pragma once
 #include <type_traits>
-#ifndef SEKA_B_SCHED
-#define SEKA_B_SCHED 1
-#endif
 
 #include "attn_bf16_lds_dma.h"
 

@@ -133,6 +133,20 @@ seka_status seka_edit_keys(const void* K_in, void* K_out, const seka_shape* sh,
                            const seka_steer* st, void* hip_stream);
 
 /*
+ * seka_edit_keys_packed — seka_edit_keys for prompts stored back to back (the layout of
+ * seka_attention_prefill_packed), so that the edited keys of an unpadded batch can persist in its cache with
+ * per-prompt expert weights (paper Sec. 3.3: the routing coefficients differ per prompt).
+ *
+ * K_in, K_out  dev [total_tokens,Hkv,D]; K_out == K_in allowed, any other overlap is SEKA_ERR_ALIAS.
+ * cu_seqlens   dev [B+1] int32, ascending, cu[0] = 0, cu[B] <= total_tokens: prompt b is rows cu[b] .. cu[b+1]-1.
+ *              Offsets are clamped into the tensor on the device; rows that belong to no prompt, and rows of a
+ *              prompt beyond sh->S (the longest prompt the launch covers), are not touched.
+ * st->mask     dev [total_tokens]; st->w dev [B,Hkv,M] (indexed by prompt).  Everything else as seka_edit_keys.
+ */
+seka_status seka_edit_keys_packed(const void* K_in, void* K_out, const seka_shape* sh, const seka_steer* st,
+                                  const int32_t* cu_seqlens, int64_t total_tokens, void* hip_stream);
+
+/*
  * seka_attention_prefill — causal attention on the edited keys, edit fused in (paper Sec. 2 and
  * Eq. 5: logits_ij = q_i . k'_j / sqrt(d_k), j <= i; softmax over j; O_i = sum_j p_ij v_j).
  * K itself is not modified: edited keys exist only on chip.

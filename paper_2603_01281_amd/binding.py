@@ -51,6 +51,8 @@ lib.seka_route_workspace_bytes.restype = _sz
 lib.seka_route_workspace_bytes.argtypes = [_shape_p, _i32, _i32]
 lib.seka_route.restype = _i32
 lib.seka_route.argtypes = [_vp, _shape_p, _vp, _i32, _i32, _i32, _i32, _f32, _vp, _vp, _sz, _vp]
+lib.seka_edit_keys_packed.restype = _i32
+lib.seka_edit_keys_packed.argtypes = [_vp, _vp, _shape_p, _steer_p, _vp, ctypes.c_int64, _vp]
 lib.seka_route_ragged_workspace_bytes.restype = _sz
 lib.seka_route_ragged_workspace_bytes.argtypes = [_shape_p, _i32]
 lib.seka_route_ragged.restype = _i32
@@ -191,6 +193,17 @@ def seka_edit_keys(K_in, K_out, U, gain, mask, w=None, stream=None, key_scale=No
     sh = _shape(B, S, Hkv, Hkv, D, _dtype_code(K_in), 0.0)
     st = _steer(U, gain, mask, w, Hkv, key_scale)
     _check(lib.seka_edit_keys(_dev(K_in, "K_in"), _dev(K_out, "K_out"), ctypes.byref(sh), ctypes.byref(st), _stream(stream)))
+    return K_out
+
+
+def seka_edit_keys_packed(K_in, K_out, cu_seqlens, max_len, U, gain, mask, w=None, stream=None, key_scale=None):
+    """Unpadded batch: K_in/K_out [total,Hkv,D], mask [total], w [B,Hkv,M]; cu_seqlens [B+1] int32 device tensor."""
+    total, Hkv, D = K_in.shape
+    B = cu_seqlens.numel() - 1
+    sh = _shape(B, max_len, Hkv, Hkv, D, _dtype_code(K_in), 0.0)
+    st = _steer(U, gain, mask, w, Hkv, key_scale)
+    _check(lib.seka_edit_keys_packed(_dev(K_in, "K_in"), _dev(K_out, "K_out"), ctypes.byref(sh), ctypes.byref(st),
+                                     _dev(cu_seqlens, "cu_seqlens"), total, _stream(stream)))
     return K_out
 
 

@@ -208,6 +208,25 @@ seka_status seka_edit_keys(const void* K_in, void* K_out, const seka_shape* sh, 
   return launch_status(e);
 }
 
+seka_status seka_edit_keys_packed(const void* K_in, void* K_out, const seka_shape* sh, const seka_steer* st,
+                                  const int32_t* cu_seqlens, int64_t total_tokens, void* hip_stream) {
+  seka_status rc = check_shape(sh, false);
+  if (rc != SEKA_OK) return rc;
+  if (!K_in || !K_out || !st || !cu_seqlens) return SEKA_ERR_NULL;
+  rc = check_steer(st, sh);
+  if (rc != SEKA_OK) return rc;
+  if (total_tokens < 1 || total_tokens > 0x7fffffffLL) return SEKA_ERR_SHAPE;
+  if (misaligned(K_in) || misaligned(K_out) || (reinterpret_cast<uintptr_t>(cu_seqlens) & 3u)) return SEKA_ERR_ALIGN;
+  const size_t nk = (size_t)total_tokens * sh->Hkv * sh->D * elem_size(sh->dtype);
+  if (K_in != K_out && ranges_overlap(K_in, nk, K_out, nk)) return SEKA_ERR_ALIAS;
+  seka::SteerArgs sa;
+  fill_steer(sa, st, sh->Hkv);
+  (void)hipGetLastError();
+  hipError_t e = seka::launch_edit_keys(K_in, K_out, sh->B, sh->S, sh->Hkv, sh->D, sh->dtype, sa,
+                                        reinterpret_cast<hipStream_t>(hip_stream), cu_seqlens, (int)total_tokens);
+  return launch_status(e);
+}
+
 size_t seka_decode_workspace_bytes(const seka_shape* sh) {
   if (check_shape(sh, true) != SEKA_OK) return 0;
   return seka::decode_workspace_bytes(sh->B, sh->S, sh->Hq, sh->Hkv, sh->D);

@@ -26,10 +26,23 @@ __device__ __forceinline__ int perm_col(int r) {
   return (r & ~31) + 8 * ((r & 15) >> 2) + 4 * ((r & 31) >> 4) + (r & 3);
 }
 
+// First token row and length of prompt b: rows b*S .. b*S+S-1 of a padded batch, or rows cu[b] .. cu[b+1]-1 of a
+// packed one (offsets clamped into the tensor, lengths to [0, S]).
+__device__ __forceinline__ void edit_prompt_extent(const int* __restrict__ cu, int total, int b, int S, size_t& tok0, int& len) {
+  tok0 = (size_t)b * S;
+  len = S;
+  if (cu != nullptr) {
+    const int start = min(max(cu[b], 0), total);
+    len = min(max(min(cu[b + 1] - start, total - start), 0), S);
+    tok0 = (size_t)start;
+  }
+}
+
 template <int D>
 __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint16_t* __restrict__ K_in,
                                                                       uint16_t* __restrict__ K_out, int S, int Hkv,
-                                                                      SteerArgs st, int inplace, int Rpad) {
+                                                                      SteerArgs st, int inplace, int Rpad,
+                                                                      const int* __restrict__ cu, int total) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int UT_LD = D + 8;                 // row stride of U^T [Rpad][D] in elements
   const int UN_LD = Rpad + 8;                  // row stride of U (column-permuted) [D][Rpad]
@@ -41,8 +54,11 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int j = lane & 15, g = lane >> 4;
   const int t = blockIdx.x * kEditTokens + wave * 16 + j;
-  const bool valid = t < S;
-  const int mk = valid ? st.mask[(size_t)b * S + t] : 0;
+  size_t tok0;
+  int len;
+  edit_prompt_extent(cu, total, b, S, tok0, len);
+  const bool valid = t < len;
+  const int mk = valid ? st.mask[tok0 + t] : 0;
   const float gain = st.gain[h];
   const float kscale = st.kscale[h];
   const bool wave_hl = __ballot(mk != 0) != 0ull;
@@ -51,7 +67,7 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint
 
   constexpr int KS = D / 32;
   bf16x8 kreg[KS];
-  const size_t row_off = (((size_t)b * S + (valid ? t : 0)) * Hkv + h) * D;
+  const size_t row_off = ((tok0 + (valid ? t : 0)) * Hkv + h) * D;
 #pragma unroll
   for (int s = 0; s < KS; ++s) {
     uint4 v = make_uint4(0, 0, 0, 0);
@@ -167,7 +183,8 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint
 template <int D>
 __global__ __launch_bounds__(kEditThreads) void edit_keys_f32_kernel(const float* __restrict__ K_in,
                                                                      float* __restrict__ K_out, int S, int Hkv,
-                                                                     SteerArgs st, int inplace) {
+                                                                     SteerArgs st, int inplace,
+                                                                     const int* __restrict__ cu, int total) {
   constexpr int TT = 16;
   __shared__ float ktile[TT][D];
   __shared__ float z[TT][SEKA_MAX_RANK];
@@ -177,17 +194,20 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_f32_kernel(const float
   const float gain = st.gain[h];
   const float kscale = st.kscale[h];
   const int R = st.M * st.r;
+  size_t tok0;
+  int len;
+  edit_prompt_extent(cu, total, b, S, tok0, len);
   int any = 0;
   if (threadIdx.x < TT) {
     const int t = t0 + threadIdx.x;
-    const int mk = (t < S) ? st.mask[(size_t)b * S + t] : 0;
+    const int mk = (t < len) ? st.mask[tok0 + t] : 0;
     mtile[threadIdx.x] = mk;
     any = mk != 0;
   }
   const bool steered = __syncthreads_or(any) != 0 && gain != 0.f;
   for (int i = threadIdx.x; i < TT * D; i += kEditThreads) {
     const int tt = i / D, d = i % D, t = t0 + tt;
-    ktile[tt][d] = (t < S) ? K_in[(((size_t)b * S + t) * Hkv + h) * D + d] : 0.f;
+    ktile[tt][d] = (t < len) ? K_in[((tok0 + t) * Hkv + h) * D + d] : 0.f;
   }
   __syncthreads();
   if (steered) {
@@ -206,7 +226,7 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_f32_kernel(const float
   }
   for (int i = threadIdx.x; i < TT * D; i += kEditThreads) {
     const int tt = i / D, d = i % D, t = t0 + tt;
-    if (t >= S) continue;
+    if (t >= len) continue;
     float v = ktile[tt][d];
     const bool edited = steered && mtile[tt];
     if (edited) {
@@ -218,14 +238,14 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_f32_kernel(const float
       }
       v = fmaf(kscale, v, acc);
     }
-    if (!inplace || edited) K_out[(((size_t)b * S + t) * Hkv + h) * D + d] = v;
+    if (!inplace || edited) K_out[((tok0 + t) * Hkv + h) * D + d] = v;
   }
 }
 
 }  // namespace
 
 hipError_t launch_edit_keys(const void* K_in, void* K_out, int B, int S, int Hkv, int D, int dtype,
-                            const SteerArgs& steer, hipStream_t s) {
+                            const SteerArgs& steer, hipStream_t s, const int* cu, int total) {
   const int inplace = (K_in == K_out) ? 1 : 0;
   if (dtype == SEKA_BF16) {
     const int R = steer.M * steer.r;
@@ -237,7 +257,7 @@ hipError_t launch_edit_keys(const void* K_in, void* K_out, int B, int S, int Hkv
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
       if (e != hipSuccess) return e;
       hipLaunchKernelGGL(kernel, grid, dim3(kEditThreads), smem, s, static_cast<const uint16_t*>(K_in),
-                         static_cast<uint16_t*>(K_out), S, Hkv, steer, inplace, Rpad);
+                         static_cast<uint16_t*>(K_out), S, Hkv, steer, inplace, Rpad, cu, total);
       return hipGetLastError();
     };
     return D == 128 ? launch(edit_keys_bf16_kernel<128>) : launch(edit_keys_bf16_kernel<64>);
@@ -245,10 +265,10 @@ hipError_t launch_edit_keys(const void* K_in, void* K_out, int B, int S, int Hkv
   const dim3 grid((S + 15) / 16, Hkv, B);
   if (D == 128)
     hipLaunchKernelGGL(edit_keys_f32_kernel<128>, grid, dim3(kEditThreads), 0, s, static_cast<const float*>(K_in),
-                       static_cast<float*>(K_out), S, Hkv, steer, inplace);
+                       static_cast<float*>(K_out), S, Hkv, steer, inplace, cu, total);
   else
     hipLaunchKernelGGL(edit_keys_f32_kernel<64>, grid, dim3(kEditThreads), 0, s, static_cast<const float*>(K_in),
-                       static_cast<float*>(K_out), S, Hkv, steer, inplace);
+                       static_cast<float*>(K_out), S, Hkv, steer, inplace, cu, total);
   return hipGetLastError();
 }
 

@@ -23,7 +23,7 @@ def test_exports_every_declared_symbol(B):
             "seka_route_workspace_bytes", "seka_status_string", "seka_set_tuning",
             "seka_attention_decode", "seka_decode_workspace_bytes", "seka_attention_prefill_ragged",
             "seka_learn_workspace_bytes", "seka_learn_projection", "seka_head_distance",
-            "seka_attention_prefill_packed", "seka_route_ragged", "seka_route_ragged_workspace_bytes"} <= names
+            "seka_attention_prefill_packed", "seka_route_ragged", "seka_route_ragged_workspace_bytes", "seka_edit_keys_packed"} <= names
     for n in names:
         assert hasattr(B.lib, n), f"libseka.so does not export {n}"
 
@@ -92,6 +92,11 @@ def test_steering_rejects_bad_arguments(B):
     assert L.seka_edit_keys(FAKE, FAKE + 64, ctypes.byref(ok), ctypes.byref(st), None) == 5
     assert L.seka_edit_keys(FAKE, None, ctypes.byref(ok), ctypes.byref(st), None) == 1
     assert L.seka_edit_keys(FAKE, FAKE, ctypes.byref(ok), None, None) == 1
+    # packed layout: offsets are required, the row count must be positive, partial overlap is refused
+    assert L.seka_edit_keys_packed(FAKE, FAKE, ctypes.byref(ok), ctypes.byref(st), None, 100, None) == 1
+    assert L.seka_edit_keys_packed(FAKE, FAKE, ctypes.byref(ok), ctypes.byref(st), FAKE * 9, 0, None) == 2
+    assert L.seka_edit_keys_packed(FAKE, FAKE, ctypes.byref(ok), ctypes.byref(st), FAKE * 9 + 1, 100, None) == 4
+    assert L.seka_edit_keys_packed(FAKE, FAKE + 64, ctypes.byref(ok), ctypes.byref(st), FAKE * 9, 100, None) == 5
 
 
 def test_route_rejects_bad_arguments(B):

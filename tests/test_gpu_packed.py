@@ -139,3 +139,51 @@ def test_route_ragged(seka, dtype):
     # equal lengths and the whole prompt: the same numbers as seka_route
     full = torch.full((B,), S, dtype=torch.int32, device="cuda")
     assert torch.equal(seka.seka_route_ragged(Qd, pd, S, seq_lens=full), seka.seka_route(Qd, pd, 0, S))
+
+
+@pytest.mark.parametrize("name", ["bf16_D128_dense_experts", "bf16_D128_odd_starts", "f32_D64"])
+def test_packed_edit_keys(seka, name):
+    """seka_edit_keys_packed against the oracle's edit, prompt by prompt with that prompt's expert weights; rows
+    that belong to no prompt stay as they were, out of place and in place."""
+    import torch
+    dtype, Hq, Hkv, D, M, r, lens, extra, max_len = CASES[name]
+    B, Smax = len(lens), max(lens)
+    print(f"packed edit {name}", flush=True)
+    inp = inputs.make_layer("packed_edit", dtype, B=B, S=Smax, Hq=Hq, Hkv=Hkv, D=D, M=M, r=r, gain=1.25,
+                            mask_recipe=("cover", 0.3, 0.3, 4), seed=29)
+    o = H.oracle_inputs(inp)
+    dev = H.DeviceInputs(inp)
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    total = int(cu[-1]) + extra
+    pack = lambda t: torch.cat([t[b, :n] for b, n in enumerate(lens)] + [t[0, :extra]], dim=0).contiguous()
+    Kp, maskp = pack(dev.K), pack(dev.mask)
+    if extra:
+        maskp[cu[-1]:] = 1                                # a set bit outside every prompt must not edit anything
+    w, w_np = None, None
+    if M > 1:
+        g = np.random.default_rng(6)
+        w_np = g.random((B, Hkv, M)).astype(np.float32)
+        w_np /= w_np.sum(-1, keepdims=True)
+        w = torch.from_numpy(w_np).cuda()
+    cu_dev = torch.from_numpy(cu).cuda()
+    K_out = torch.full_like(Kp, float("nan"))
+    seka.seka_edit_keys_packed(Kp, K_out, cu_dev, max_len, dev.U, dev.gain, maskp, w=w)
+    K_io = Kp.clone()
+    seka.seka_edit_keys_packed(K_io, K_io, cu_dev, max_len, dev.U, dev.gain, maskp, w=w)
+    torch.cuda.synchronize()
+    got, got_io = H.to_f64(K_out), H.to_f64(K_io)
+    assert np.isnan(got[cu[-1]:]).all()                   # nobody's rows: not written
+    assert np.array_equal(got_io[cu[-1]:], H.to_f64(Kp)[cu[-1]:])
+    changed = False
+    for b, n in enumerate(lens):
+        if n == 0:
+            continue
+        ref = orc.edit_keys(o["K"][b:b + 1, :n], o["U"], inp.gain, inp.mask[b:b + 1, :n],
+                            w=None if w_np is None else w_np[b:b + 1].astype(np.float64))[0]
+        for res, what in ((got[cu[b]:cu[b + 1]], "out of place"), (got_io[cu[b]:cu[b + 1]], "in place")):
+            if dtype == "bf16":
+                H.assert_edit_close_bf16(res, ref, 1.25, f"{name} prompt {b} {what}")
+            else:
+                assert np.abs(res - ref).max() <= H.F32_ABS, (name, b, what)
+        changed |= bool(np.abs(ref - o["K"][b, :n]).max() > 1e-3)
+    assert changed

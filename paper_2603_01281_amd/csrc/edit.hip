@@ -1,7 +1,7 @@
 // seka_edit_keys: standalone key-editing hook (paper Algorithm 1/2, inference part):
 //   k' = k + g * sum_m w_m U_m (U_m^T k)   on highlighted tokens of selected heads.
 //
-// HBM-bound (read K once, write K' once).  bf16 path: one workgroup = 64 tokens of one KV head,
+// HBM-bound (read K once, write K' once).  bf16 path: one tile = 64 tokens of one KV head,
 // one wave = 16 tokens.  A wave keeps its 16 x D key tile in registers in exactly the layout the
 // 16x16x32 bf16 MFMA wants for its B operand, so the two small GEMMs
 //   Z^T = U_cat^T K^T   (R x 16, contraction over D)      and
@@ -9,7 +9,9 @@
 // run on the matrix cores without moving the keys again, and the correction lands in the same
 // lanes that hold the matching key elements (the row order of U fed to the second GEMM is
 // permuted to make that so).  Tiles without highlighted tokens are a plain 16-byte copy (or are
-// skipped entirely when editing in place).  U is staged in LDS only by workgroups that need it.
+// skipped entirely when editing in place).  U is staged in LDS only by workgroups that need it; at large
+// ranks (a 70 KB staging area, two workgroups per CU) a workgroup takes several tiles in turn, stages once and
+// keeps the next tile's keys in flight while it works on the current one.
 #include "common.h"
 
 namespace seka {
@@ -42,7 +44,7 @@ template <int D>
 __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint16_t* __restrict__ K_in,
                                                                       uint16_t* __restrict__ K_out, int S, int Hkv,
                                                                       SteerArgs st, int inplace, int Rpad,
-                                                                      const int* __restrict__ cu, int total) {
+                                                                      const int* __restrict__ cu, int total, int tpw) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int UT_LD = D + 8;                 // row stride of U^T [Rpad][D] in elements
   const int UN_LD = Rpad + 8;                  // row stride of U (column-permuted) [D][Rpad]
@@ -53,27 +55,47 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint
   const int b = blockIdx.z, h = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int j = lane & 15, g = lane >> 4;
-  const int t = blockIdx.x * kEditTokens + wave * 16 + j;
   size_t tok0;
   int len;
   edit_prompt_extent(cu, total, b, S, tok0, len);
-  const bool valid = t < len;
-  const int mk = valid ? st.mask[tok0 + t] : 0;
   const float gain = st.gain[h];
   const float kscale = st.kscale[h];
+  // A workgroup takes `tpw` consecutive 64-token tiles (one for small ranks; several for large ones, whose
+  // operand staging is expensive and whose LDS footprint leaves few workgroups per CU): U is staged at the first
+  // tile that needs it, and the next tile's keys are requested before the current one is worked on.
+  const int tile_first = blockIdx.x * tpw;
+  if (tile_first * kEditTokens >= len) return;           // workgroup-uniform, before any barrier
+  const int ntile = min(tpw, (len - tile_first * kEditTokens + kEditTokens - 1) / kEditTokens);
+  constexpr int KS = D / 32;
+  auto fetch = [&](int tile, int& mk_o, bool& valid_o, size_t& off_o, bf16x8 (&kr)[KS]) __attribute__((always_inline)) {
+    const int t = tile * kEditTokens + wave * 16 + j;
+    valid_o = t < len;
+    mk_o = valid_o ? st.mask[tok0 + t] : 0;
+    off_o = ((tok0 + (valid_o ? t : 0)) * Hkv + h) * D;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (valid_o) v = *reinterpret_cast<const uint4*>(K_in + off_o + 32 * s + 8 * g);
+      kr[s] = __builtin_bit_cast(bf16x8, v);
+    }
+  };
+  int mk_n;
+  bool valid_n;
+  size_t off_n;
+  bf16x8 kn[KS];
+  fetch(tile_first, mk_n, valid_n, off_n, kn);
+  bool staged = false;                                   // workgroup-uniform
+  for (int ti = 0; ti < ntile; ++ti) {
+  const int mk = mk_n;
+  const bool valid = valid_n;
+  const size_t row_off = off_n;
+  bf16x8 kreg[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) kreg[s] = kn[s];
+  if (ti + 1 < ntile) fetch(tile_first + ti + 1, mk_n, valid_n, off_n, kn);
   const bool wave_hl = __ballot(mk != 0) != 0ull;
   const bool block_hl = __syncthreads_or(mk != 0) != 0;
   const bool steered = block_hl && gain != 0.f;
-
-  constexpr int KS = D / 32;
-  bf16x8 kreg[KS];
-  const size_t row_off = ((tok0 + (valid ? t : 0)) * Hkv + h) * D;
-#pragma unroll
-  for (int s = 0; s < KS; ++s) {
-    uint4 v = make_uint4(0, 0, 0, 0);
-    if (valid) v = *reinterpret_cast<const uint4*>(K_in + row_off + 32 * s + 8 * g);
-    kreg[s] = __builtin_bit_cast(bf16x8, v);
-  }
 
   if (!steered) {
     if (!inplace && valid) {
@@ -81,11 +103,13 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint
       for (int s = 0; s < KS; ++s)
         *reinterpret_cast<uint4*>(K_out + row_off + 32 * s + 8 * g) = __builtin_bit_cast(uint4, kreg[s]);
     }
-    return;
+    continue;
   }
 
   // ---- stage U (both orientations) and the per-column coefficients in LDS ----
   const int R = st.M * st.r;
+  if (!staged) {
+  staged = true;
   if (R != Rpad) {
     for (int i = threadIdx.x; i < (Rpad - R) * UT_LD; i += kEditThreads) UT[(size_t)R * UT_LD + i] = 0;
     for (int i = threadIdx.x; i < D * UN_LD; i += kEditThreads) UN[i] = 0;
@@ -94,8 +118,8 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint
   {
     const uint16_t* Uh = reinterpret_cast<const uint16_t*>(st.U) + (size_t)h * st.M * D * st.r;
     const int r8 = st.r / 8;
-    const int total = st.M * D * r8;
-    for (int idx = threadIdx.x; idx < total; idx += kEditThreads) {
+    const int pieces = st.M * D * r8;
+    for (int idx = threadIdx.x; idx < pieces; idx += kEditThreads) {
       const int m = idx / (D * r8), rem = idx % (D * r8);
       const int d = rem / r8, v = rem % r8;
       const uint4 u = *reinterpret_cast<const uint4*>(Uh + ((size_t)m * D + d) * st.r + 8 * v);
@@ -114,6 +138,7 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint
     }
   }
   __syncthreads();
+  }
 
   if (!wave_hl) {
     if (!inplace && valid) {
@@ -121,7 +146,7 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint
       for (int s = 0; s < KS; ++s)
         *reinterpret_cast<uint4*>(K_out + row_off + 32 * s + 8 * g) = __builtin_bit_cast(uint4, kreg[s]);
     }
-    return;
+    continue;
   }
 
   // ---- Z^T = U^T K^T, scaled by c_r and by the token's mask bit; packed as the next B operand ----
@@ -177,6 +202,7 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint
     if (valid && (!inplace || mk != 0))
       *reinterpret_cast<uint4*>(K_out + row_off + 32 * s + 8 * g) = __builtin_bit_cast(uint4, o);
   }
+  }   // tiles of this workgroup
 }
 
 // fp32 path (small problems, exactness over speed): one workgroup = 16 tokens of one KV head.
@@ -251,13 +277,17 @@ hipError_t launch_edit_keys(const void* K_in, void* K_out, int B, int S, int Hkv
     const int R = steer.M * steer.r;
     const int Rpad = (R + 31) / 32 * 32;
     const size_t smem = ((size_t)Rpad * (D + 8) + (size_t)D * (Rpad + 8)) * 2 + (size_t)Rpad * 4;
-    const dim3 grid((S + kEditTokens - 1) / kEditTokens, Hkv, B);
+    const int tiles = (S + kEditTokens - 1) / kEditTokens;
+    // Tiles per workgroup (see the kernel): four at rank > 64 when that still leaves 1024 workgroups (measured at
+    // 8 prompts x 4096 tokens x 8 heads, rank 128: 37 us against 47 us with one; one is best everywhere else).
+    const int tpw = (Rpad > 64 && (long long)tiles * Hkv * B >= 4096) ? 4 : 1;
+    const dim3 grid((tiles + tpw - 1) / tpw, Hkv, B);
     auto launch = [&](auto kernel) -> hipError_t {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
       if (e != hipSuccess) return e;
       hipLaunchKernelGGL(kernel, grid, dim3(kEditThreads), smem, s, static_cast<const uint16_t*>(K_in),
-                         static_cast<uint16_t*>(K_out), S, Hkv, steer, inplace, Rpad, cu, total);
+                         static_cast<uint16_t*>(K_out), S, Hkv, steer, inplace, Rpad, cu, total, tpw);
       return hipGetLastError();
     };
     return D == 128 ? launch(edit_keys_bf16_kernel<128>) : launch(edit_keys_bf16_kernel<64>);

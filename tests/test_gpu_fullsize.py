@@ -83,6 +83,15 @@ def test_cfg4_full_size_routed(seka):
     assert np.abs(H.to_f64(w) - ref_w).max() <= H.ROUTE_ABS
     rows = H.sample_rows(inp, per_head=6, seed=3)
     _check_rows(seka, inp, dev, rows, w_dev=w, w_ref=ref_w, steered=True, what="cfg4 steered")
+    # standalone edit at full size (rank 128: a workgroup takes several 64-token tiles), compared in full, out of
+    # place and in place
+    ref_K = orc.edit_keys(inp.widen(inp.K), inp.widen(inp.U), inp.gain, inp.mask, w=ref_w)
+    K_out = torch.empty_like(dev.K)
+    seka.seka_edit_keys(dev.K, K_out, dev.U, dev.gain, dev.mask, w=w)
+    H.assert_edit_close_bf16(H.to_f64(K_out), ref_K, float(np.abs(inp.gain).max()), "cfg4 edit")
+    K_io = dev.K.clone()
+    seka.seka_edit_keys(K_io, K_io, dev.U, dev.gain, dev.mask, w=w)
+    assert torch.equal(K_io, K_out), "cfg4 edit in place differs from out of place"
 
 
 def test_cfg5_full_size(seka):

@@ -856,7 +856,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   // tile runs the same pipelined step with run-time ring offsets and guarded loads (a slower tile).
   // Steering events (a tile to edit, a summary word to reload) are handled inside the hot loop, except in the
   // one shape where that measured slower than leaving the loop for the slower tile: the dense edit with seven
-  // waves (cfg5: 3 % faster outside; cfg4, dense with eight waves: 3 % faster inside).
+  // waves (Hq=28, Hkv=4, rank 64: 3 % faster outside; dense with eight waves: 3 % faster inside).
   const int t_hot = min(tw_last, min(ntiles, S / BK) - 2);
   int t = 0;
 #pragma nounroll

@@ -117,19 +117,29 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint
   }
   {
     const uint16_t* Uh = reinterpret_cast<const uint16_t*>(st.U) + (size_t)h * st.M * D * st.r;
+    // A thread takes the same 8 columns of four consecutive rows d (four 16-byte pieces of U), so that the
+    // transposed copy is written 8 bytes at a time instead of 2.
     const int r8 = st.r / 8;
-    const int pieces = st.M * D * r8;
-    for (int idx = threadIdx.x; idx < pieces; idx += kEditThreads) {
-      const int m = idx / (D * r8), rem = idx % (D * r8);
-      const int d = rem / r8, v = rem % r8;
-      const uint4 u = *reinterpret_cast<const uint4*>(Uh + ((size_t)m * D + d) * st.r + 8 * v);
+    const int quads = st.M * (D / 4) * r8;
+    for (int idx = threadIdx.x; idx < quads; idx += kEditThreads) {
+      const int m = idx / ((D / 4) * r8), rem = idx % ((D / 4) * r8);
+      const int d0 = 4 * (rem / r8), v = rem % r8;
       const int r0 = m * st.r + 8 * v;
-      const uint32_t wds[4] = {u.x, u.y, u.z, u.w};
+      uint32_t wds[4][4];
 #pragma unroll
-      for (int e = 0; e < 8; ++e)
-        UT[(size_t)(r0 + e) * UT_LD + d] = (uint16_t)((wds[e >> 1] >> (16 * (e & 1))) & 0xffffu);
-      *reinterpret_cast<uint2*>(UN + (size_t)d * UN_LD + perm_col(r0)) = make_uint2(u.x, u.y);
-      *reinterpret_cast<uint2*>(UN + (size_t)d * UN_LD + perm_col(r0 + 4)) = make_uint2(u.z, u.w);
+      for (int q = 0; q < 4; ++q) {
+        const uint4 u = *reinterpret_cast<const uint4*>(Uh + ((size_t)m * D + d0 + q) * st.r + 8 * v);
+        wds[q][0] = u.x; wds[q][1] = u.y; wds[q][2] = u.z; wds[q][3] = u.w;
+        *reinterpret_cast<uint2*>(UN + (size_t)(d0 + q) * UN_LD + perm_col(r0)) = make_uint2(u.x, u.y);
+        *reinterpret_cast<uint2*>(UN + (size_t)(d0 + q) * UN_LD + perm_col(r0 + 4)) = make_uint2(u.z, u.w);
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int sh = 16 * (e & 1);
+        const uint32_t lo = ((wds[0][e >> 1] >> sh) & 0xffffu) | (((wds[1][e >> 1] >> sh) & 0xffffu) << 16);
+        const uint32_t hi = ((wds[2][e >> 1] >> sh) & 0xffffu) | (((wds[3][e >> 1] >> sh) & 0xffffu) << 16);
+        *reinterpret_cast<uint2*>(UT + (size_t)(r0 + e) * UT_LD + d0) = make_uint2(lo, hi);
+      }
     }
     for (int r = threadIdx.x; r < Rpad; r += kEditThreads) {
       float c = 0.f;

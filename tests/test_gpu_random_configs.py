@@ -67,3 +67,29 @@ def test_random_configuration(seka, case):
                                              key_scale=None if ks is None else ks.astype(np.float64))
         H.assert_close_bf16(got_O[b:b + 1, :n], ref_O, f"case {case} prompt {b} O")
         H.assert_lse_close_bf16(got_L[b:b + 1, :, :n], ref_L, f"case {case} prompt {b} LSE")
+
+
+@pytest.mark.parametrize("mult", [0.02, 3.0, 6.0])
+def test_score_scales(seka, mult):
+    """Nearly flat and very sharp softmax rows (scores ~ mult^2 * N(0, 1) * sqrt(D) * scale): the reference exponent
+    of the online softmax is raised late and in jumps of any size, rows are dominated by one key or by none."""
+    import torch
+    print(f"score scale: inputs x {mult}", flush=True)
+    inp = inputs.make_layer("scales", "bf16", B=2, S=700, Hq=8, Hkv=2, D=128, M=1, r=32, gain=1.0,
+                            mask_recipe=("cover", 0.3, 0.3, 3), seed=77, qkv_mult=mult)
+    dev = H.DeviceInputs(inp)
+    o = H.oracle_inputs(inp)
+    O = torch.full_like(dev.Q, float("nan"))
+    lse = torch.full((2, 8, 700), float("nan"), dtype=torch.float32, device="cuda")
+    seka.seka_attention_prefill(dev.Q, dev.K, dev.V, O, dev.U, dev.gain, dev.mask, lse=lse, scale=inp.scale)
+    torch.cuda.synchronize()
+    ref_O, ref_L = orc.steered_attention(o["Q"], o["K"], o["V"], o["U"], inp.gain, inp.mask, scale=inp.scale)
+    got_O, got_L = H.to_f64(O), H.to_f64(lse)
+    assert np.isfinite(got_O).all() and np.isfinite(got_L).all()
+    # outputs are convex combinations of V rows, so the absolute bound scales with the inputs; a sharp row moves
+    # by one key's bf16 score error times its weight, which the bound for unit inputs covers after that scaling
+    s = max(1.0, mult)
+    d = np.abs(got_O - ref_O)
+    assert d.max() <= H.BF16_MAX * s * max(1.0, mult ** 2), f"max |dO| {d.max():.4g}"
+    assert d.mean() <= H.BF16_MEAN * s * max(1.0, mult ** 2), f"mean |dO| {d.mean():.4g}"
+    print(f"mult {mult}: max |dO| {d.max():.4g} mean {d.mean():.4g}; max |dLSE| {np.abs(got_L - ref_L).max():.4g}", flush=True)

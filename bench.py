@@ -176,6 +176,20 @@ def time_learn(torch, seka, inputs, n=16384, Hkv=8, D=128, iters=5):
             "head_distance_ms": round(dist_ms, 4), "head_distance_GBps": round(2 * ha.numel() * 2 / dist_ms / 1e6, 1)}
 
 
+def mfma_only_rate(torch):
+    """What a loop of bf16 MFMAs alone sustains on this device with constant and with random operands (a stand-alone
+    probe built next to the library): context for the roofline fraction, which is quoted against the published peak."""
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2603_01281_amd", "mfma_rate_probe.bin")
+    if not os.path.exists(exe):
+        return None
+    torch.cuda.synchronize()
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    if r.returncode != 0:
+        return {"error": r.stderr.strip()[-200:]}
+    return json.loads(r.stdout.strip().splitlines()[-1])
+
+
 def paired_medians(torch, fn_a, fn_b, flops, n=15):
     for _ in range(max(10, int(120.0 / (flops / 1.0e12)))):      # ~1 PFLOP/s => ms per launch ~ flops / 1e12
         fn_a()
@@ -278,6 +292,7 @@ def main():
     if args.extras:
         out["other_configs"] = {f"cfg{c}": time_config(torch, seka, inputs, c) for c in (2, 3, 4, 5)}
         out["offline_learn"] = time_learn(torch, seka, inputs)
+        out["mfma_only_rate"] = mfma_only_rate(torch)
     del layers
     torch.cuda.empty_cache()
     if not args.no_cpu_baseline:

@@ -168,7 +168,7 @@ def time_learn(torch, seka, inputs, n=16384, Hkv=8, D=128, iters=5):
     sg = torch.empty((Hkv, D), device="cuda")
     k = torch.empty((Hkv,), dtype=torch.int32, device="cuda")
     Up = torch.empty((Hkv, D, 32), device="cuda", dtype=torch.bfloat16)
-    ws = torch.empty(1 << 24, dtype=torch.uint8, device="cuda")
+    ws = torch.empty(max(seka.seka_learn_workspace_bytes(1, n, Hkv, D, seka.SEKA_BF16), 16), dtype=torch.uint8, device="cuda")
     dist = torch.empty((Hkv,), device="cuda")
     learn_ms = event_time(torch, lambda: seka.seka_learn_projection(ha, hb, 0.9, U, sg, k, U_packed=Up, workspace=ws), iters)
     dist_ms = event_time(torch, lambda: seka.seka_head_distance(ha, hb, dist, workspace=ws), iters)

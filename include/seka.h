@@ -232,6 +232,9 @@ seka_status seka_attention_decode(const void* q, const void* K, const void* V, v
  *            columns zero, ready to be seka_steer.U with M = 1, r = r_pad (1 <= r_pad <= D).
  * workspace  dev scratch of at least seka_learn_workspace_bytes(sh) bytes, 16-byte aligned.
  * fp32 arithmetic throughout (one-sided Jacobi iteration to a relative off-diagonal of 2e-6); deterministic.
+ * The decomposition runs one workgroup per head and is bound by its own latency, so a call costs about the
+ * same for 8 heads as for 64: heads of several layers may be stacked along the head axis of one call (Hkv <=
+ * SEKA_MAX_KV_HEADS).
  *
  * seka_head_distance — the head-selection score of Sec. 3.4: D_out[h] = (1/n) sum_t || h_pos[t,h,:] -
  * h_neg[t,h,:] ||_2 over the n = B*S sample tokens; heads whose score clears a threshold are given a nonzero

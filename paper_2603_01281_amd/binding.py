@@ -226,6 +226,11 @@ def seka_attention_plain(Q, K, V, O, lse=None, scale=0.0, stream=None):
     return O
 
 
+def seka_learn_workspace_bytes(B, S, Hkv, D, dtype):
+    sh = _shape(B, S, Hkv, Hkv, D, dtype, 0.0)
+    return lib.seka_learn_workspace_bytes(ctypes.byref(sh))
+
+
 def seka_decode_workspace_bytes(B, S, Hq, Hkv, D, dtype):
     sh = _shape(B, S, Hq, Hkv, D, dtype, 0.0)
     return lib.seka_decode_workspace_bytes(ctypes.byref(sh))

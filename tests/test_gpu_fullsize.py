@@ -100,3 +100,16 @@ def test_cfg5_full_size(seka):
     dev = H.DeviceInputs(inp)
     rows = H.sample_rows(inp, per_head=12, seed=4)
     _check_rows(seka, inp, dev, rows, steered=True, what="cfg5 steered")
+
+
+def test_very_long_prompt_takes_the_register_staged_kernel(seka):
+    """At 420k tokens the pipelined kernel's highlight bitmap no longer fits LDS beside its rings, so the steered
+    call falls back to the register-staged kernel (the plain call stays on the pipelined one); sampled rows."""
+    S = 420_000
+    _say(f"long prompt S={S}")
+    inp = inputs.make_layer("long", "bf16", B=1, S=S, Hq=4, Hkv=1, D=128, M=1, r=32, gain=1.0,
+                            mask_recipe=("lengths", 6, 64, 512), seed=61)
+    dev = H.DeviceInputs(inp)
+    rows = H.sample_rows(inp, per_head=3, seed=5)
+    _check_rows(seka, inp, dev, rows, steered=True, what="long steered")
+    _check_rows(seka, inp, dev, rows, steered=False, what="long plain")

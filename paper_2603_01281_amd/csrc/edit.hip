@@ -72,10 +72,12 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint
     valid_o = t < len;
     mk_o = valid_o ? st.mask[tok0 + t] : 0;
     off_o = ((tok0 + (valid_o ? t : 0)) * Hkv + h) * D;
+    // in place, a wave whose 16 tokens are not highlighted neither edits nor copies: it does not read its keys
+    const bool need = valid_o && !(inplace && __ballot(mk_o != 0) == 0ull);
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       uint4 v = make_uint4(0, 0, 0, 0);
-      if (valid_o) v = *reinterpret_cast<const uint4*>(K_in + off_o + 32 * s + 8 * g);
+      if (need) v = *reinterpret_cast<const uint4*>(K_in + off_o + 32 * s + 8 * g);
       kr[s] = __builtin_bit_cast(bf16x8, v);
     }
   };

@@ -125,6 +125,21 @@ def time_config(torch, seka, inputs, cfg, iters=10):
         w = seka.seka_route(Q, proto, 0, S, seka.SEKA_ROUTE_SOFTMAX_COS, 10.0)
         ws = torch.empty(seka.seka_route_workspace_bytes(B, S, Hq, Hkv, D, seka.SEKA_BF16, 0, S), dtype=torch.uint8, device="cuda")
         route_ms = event_time(torch, lambda: seka.seka_route(Q, proto, 0, S, seka.SEKA_ROUTE_SOFTMAX_COS, 10.0, w_out=w, workspace=ws), iters)
+        # the query projection with the routing in its epilogue, against projection alone + seka_route (E = Hq * D)
+        E = Hq * D
+        X = torch.randn((B, S, E), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        Wq = (torch.randn((Hq * D, E), generator=gen, device="cuda", dtype=torch.float32) / E ** 0.5).to(torch.bfloat16)
+        Qp = torch.empty_like(Q)
+        wsp = torch.empty(seka.seka_project_route_workspace_bytes(B, S, Hq, Hkv, D, seka.SEKA_BF16), dtype=torch.uint8, device="cuda")
+        fused = lambda: seka.seka_project_route(X, Wq, Qp, Hkv, proto=proto, tau=10.0, w_out=w, workspace=wsp)
+        def unfused():
+            seka.seka_project_route(X, Wq, Qp, Hkv)
+            seka.seka_route(Qp, proto, 0, S, seka.SEKA_ROUTE_SOFTMAX_COS, 10.0, w_out=w, workspace=ws)
+        gemm_flops = 2.0 * B * S * E * Hq * D
+        unf_ms, fus_ms = paired_medians(torch, unfused, fused, gemm_flops)
+        proj_extra = {"project_then_route_ms": round(unf_ms, 4), "project_route_fused_ms": round(fus_ms, 4),
+                      "project_route_fused_tflops": round(gemm_flops / fus_ms / 1e9, 1)}
+        w = seka.seka_route(Q, proto, 0, S, seka.SEKA_ROUTE_SOFTMAX_COS, 10.0)       # weights of the benchmark's own queries
     # The GPU's clock depends on recent load: warm up with both kernels for >= 100 ms, then take per-launch
     # medians of interleaved launches so that both see the same clock state.
     run_plain = lambda: seka.seka_attention_plain(Q, K, V, O)
@@ -134,6 +149,7 @@ def time_config(torch, seka, inputs, cfg, iters=10):
     out = {"plain_ms": round(plain, 4), "steered_ms": round(steer, 4), "steered_tflops": round(fl / steer / 1e9, 1),
            "overhead_pct": round(100 * (steer / plain - 1), 2), "tokens_per_s": round(B * S / steer * 1e3)}
     if route_ms is not None:
+        out.update(proj_extra)
         out["route_ms"] = round(route_ms, 4)
         out["route_GBps"] = round(B * S * Hq * D * 2 / route_ms / 1e6, 1)
     # standalone key edit, out of place: reads K and writes K' once (algorithmic bytes 2 * |K|)

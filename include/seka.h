@@ -121,6 +121,25 @@ seka_status seka_route_ragged(const void* Q, const seka_shape* sh, const float* 
                               size_t workspace_bytes, void* hip_stream);
 
 /*
+ * seka_project_route — the query projection with AdaSEKA's routing in its epilogue (paper Sec. 3.3: the
+ * routing query is formed from the layer's queries, which this projection has just produced, so the separate
+ * pass of seka_route over Q is not needed).
+ *   Q_out[b,t,hq,d] = sum_e X[b,t,e] Wq[hq*D + d, e]      (fp32 accumulation, rounded once to bf16)
+ *   w_out = seka_route(Q_out, t0 = 0, t1 = S, mode, tau)    (from the rounded values, without reading them back)
+ *
+ * X      dev [B,S,E] bf16: the layer's input tokens.     Wq  dev [Hq*D, E] bf16: one row per output feature.
+ * Q_out  dev [B,S,Hq,D] bf16 (written).                  E: a multiple of 64.
+ * w_out  dev [B,Hkv,M] fp32 or NULL (projection only; proto, M, mode, tau and the workspace are then ignored).
+ * proto, M, mode, tau as in seka_route.
+ * workspace  dev scratch of at least seka_project_route_workspace_bytes(sh) bytes, 16-byte aligned.
+ * bf16, D = 128 and S a multiple of 128 only (SEKA_ERR_UNSUPPORTED otherwise; the size call then returns 0).
+ */
+size_t seka_project_route_workspace_bytes(const seka_shape* sh);
+seka_status seka_project_route(const void* X, const void* Wq, int32_t E, void* Q_out, const seka_shape* sh,
+                               const float* proto, int32_t M, int32_t mode, float tau, float* w_out,
+                               void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
  * seka_edit_keys — the standalone key-editing hook (Algorithm 1 / 2, inference part):
  *   K_out[b,t,h,:] = K_in[b,t,h,:] + gain[h] * sum_m w[b,h,m] U[h,m] (U[h,m]^T K_in[b,t,h,:])
  * where mask[b,t] != 0 and gain[h] != 0; K_out = K_in elsewhere.

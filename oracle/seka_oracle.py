@@ -26,6 +26,8 @@ What is written out here, in the order the paper states it:
 * Sec. 3.4         D_h = mean_i || h+_i - h-_i ||_2               -> head_relevance_distance
 * generation step  the same attention for one new query per prompt over a cache of (edited) keys
                                                                   -> decode_attention
+* query projection  Q[b,t,hq,:] = W_q[hq] x[b,t,:] (the linear map whose output the routing reads, Sec. 3.3)
+                                                                  -> project_queries
 * Eq. 6            alpha_m = sum_k (q.u_m^(k)) sigma_m^(k) / max_m |.|   -> route_eq6
 * benchmark's routing rule  w = softmax_m(tau * cos(mean prompt query, prototype_m))
                                                                   -> route_softmax_cos
@@ -279,6 +281,20 @@ def mean_group_query(Q, H, t0, t1):
         for h in range(H):
             q_bar[b, h] = Q[b, t0:t1, h * G:(h + 1) * G, :].reshape(-1, d).mean(axis=0)
     return q_bar
+
+
+def project_queries(X, Wq, Hq):
+    """Q[b, t, hq, d] = sum_e X[b, t, e] Wq[hq * D + d, e]: the layer's query projection, one weight row per
+    output feature (paper Sec. 3.3 routes on these queries)."""
+    X = np.asarray(X, dtype=np.float64)
+    Wq = np.asarray(Wq, dtype=np.float64)
+    B, T, E = X.shape
+    N = Wq.shape[0]
+    assert Wq.shape[1] == E and N % Hq == 0
+    Q = np.zeros((B, T, N))
+    for n in range(N):                      # one output feature at a time: a dot product per token
+        Q[:, :, n] = X @ Wq[n]
+    return Q.reshape(B, T, Hq, N // Hq)
 
 
 def route_softmax_cos(Q, proto, t0, t1, tau):

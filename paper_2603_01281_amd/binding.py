@@ -51,6 +51,10 @@ lib.seka_route_workspace_bytes.restype = _sz
 lib.seka_route_workspace_bytes.argtypes = [_shape_p, _i32, _i32]
 lib.seka_route.restype = _i32
 lib.seka_route.argtypes = [_vp, _shape_p, _vp, _i32, _i32, _i32, _i32, _f32, _vp, _vp, _sz, _vp]
+lib.seka_project_route_workspace_bytes.restype = _sz
+lib.seka_project_route_workspace_bytes.argtypes = [_shape_p]
+lib.seka_project_route.restype = _i32
+lib.seka_project_route.argtypes = [_vp, _vp, _i32, _vp, _shape_p, _vp, _i32, _i32, _f32, _vp, _vp, _sz, _vp]
 lib.seka_edit_keys_packed.restype = _i32
 lib.seka_edit_keys_packed.argtypes = [_vp, _vp, _shape_p, _steer_p, _vp, ctypes.c_int64, _vp]
 lib.seka_route_ragged_workspace_bytes.restype = _sz
@@ -184,6 +188,34 @@ def seka_route_ragged(Q, proto, window, seq_lens=None, cu_seqlens=None, max_len=
                                  _dev(cu_seqlens, "cu_seqlens"), total, window, mode, float(tau), _dev(w_out, "w_out"),
                                  _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
                                  _stream(stream)))
+    return w_out
+
+
+def seka_project_route_workspace_bytes(B, S, Hq, Hkv, D, dtype):
+    sh = _shape(B, S, Hq, Hkv, D, dtype, 0.0)
+    return lib.seka_project_route_workspace_bytes(ctypes.byref(sh))
+
+
+def seka_project_route(X, Wq, Q_out, Hkv, proto=None, mode=SEKA_ROUTE_SOFTMAX_COS, tau=10.0, w_out=None,
+                       workspace=None, stream=None):
+    """X [B,S,E] bf16, Wq [Hq*D,E] bf16 -> Q_out [B,S,Hq,D] bf16 and, with proto [Hkv,M,D], the routing weights
+    w_out [B,Hkv,M] of the whole prompt (allocated if None).  Returns w_out (None without proto)."""
+    torch = _torch()
+    B, S, Hq, D = Q_out.shape
+    E = X.shape[2]
+    sh = _shape(B, S, Hq, Hkv, D, _dtype_code(Q_out), 0.0)
+    M = 0
+    if proto is not None:
+        M = proto.shape[1]
+        if w_out is None:
+            w_out = torch.empty((B, Hkv, M), dtype=torch.float32, device=X.device)
+        if workspace is None:
+            workspace = torch.empty(max(lib.seka_project_route_workspace_bytes(ctypes.byref(sh)), 16), dtype=torch.uint8, device=X.device)
+    else:
+        w_out = None
+    nbytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(lib.seka_project_route(_dev(X, "X"), _dev(Wq, "Wq"), E, _dev(Q_out, "Q_out"), ctypes.byref(sh), _dev(proto, "proto"),
+                                  M, mode, float(tau), _dev(w_out, "w_out"), _dev(workspace, "workspace"), nbytes, _stream(stream)))
     return w_out
 
 

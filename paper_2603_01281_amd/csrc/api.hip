@@ -190,6 +190,40 @@ seka_status seka_route_ragged(const void* Q, const seka_shape* sh, const float* 
   return launch_status(e);
 }
 
+size_t seka_project_route_workspace_bytes(const seka_shape* sh) {
+  if (check_shape(sh, true) != SEKA_OK || sh->D != 128 || sh->S % 128 != 0) return 0;
+  return seka::project_route_workspace_bytes(sh->B, sh->S, sh->Hq);
+}
+
+seka_status seka_project_route(const void* X, const void* Wq, int32_t E, void* Q_out, const seka_shape* sh,
+                               const float* proto, int32_t M, int32_t mode, float tau, float* w_out,
+                               void* workspace, size_t workspace_bytes, void* hip_stream) {
+  seka_status rc = check_shape(sh, true);
+  if (rc != SEKA_OK) return rc;
+  if (!X || !Wq || !Q_out) return SEKA_ERR_NULL;
+  if (E < 64 || E % 64 != 0) return SEKA_ERR_SHAPE;
+  if (sh->dtype != SEKA_BF16 || sh->D != 128 || sh->S % 128 != 0) return SEKA_ERR_UNSUPPORTED;
+  if ((int64_t)sh->Hq * sh->D * (int64_t)E >= ((int64_t)1 << 40)) return SEKA_ERR_SHAPE;
+  if (misaligned(X) || misaligned(Wq) || misaligned(Q_out)) return SEKA_ERR_ALIGN;
+  const size_t nx = (size_t)sh->B * sh->S * E * 2, nw = (size_t)sh->Hq * sh->D * E * 2;
+  const size_t nq = (size_t)sh->B * sh->S * sh->Hq * sh->D * 2;
+  if (ranges_overlap(Q_out, nq, X, nx) || ranges_overlap(Q_out, nq, Wq, nw)) return SEKA_ERR_ALIAS;
+  if (w_out) {
+    if (!proto) return SEKA_ERR_NULL;
+    if (M < 1 || M > SEKA_MAX_EXPERTS) return SEKA_ERR_SHAPE;
+    if (mode != SEKA_ROUTE_SOFTMAX_COS && mode != SEKA_ROUTE_PAPER_EQ6) return SEKA_ERR_UNSUPPORTED;
+    if (!std::isfinite(tau)) return SEKA_ERR_SHAPE;
+    if (misaligned(proto) || (reinterpret_cast<uintptr_t>(w_out) & 3u)) return SEKA_ERR_ALIGN;
+    const size_t need = seka::project_route_workspace_bytes(sh->B, sh->S, sh->Hq);
+    if (!workspace || workspace_bytes < need) return SEKA_ERR_WORKSPACE;
+    if (misaligned(workspace)) return SEKA_ERR_ALIGN;
+  }
+  (void)hipGetLastError();
+  hipError_t e = seka::launch_project_route(X, Wq, E, Q_out, sh->B, sh->S, sh->Hq, sh->Hkv, proto, M, mode, tau, w_out,
+                                            workspace, reinterpret_cast<hipStream_t>(hip_stream));
+  return launch_status(e);
+}
+
 seka_status seka_edit_keys(const void* K_in, void* K_out, const seka_shape* sh, const seka_steer* st,
                            void* hip_stream) {
   seka_status rc = check_shape(sh, false);

@@ -46,6 +46,10 @@ bool attention_bf16_variant_ok(int variant);
 hipError_t launch_edit_keys(const void* K_in, void* K_out, int B, int S, int Hkv, int D, int dtype,
                             const SteerArgs& steer, hipStream_t s, const int* cu = nullptr, int total = 0);
 size_t route_workspace_bytes(int B, int Hkv, int D, int t0, int t1);
+size_t project_route_workspace_bytes(int B, int S, int Hq);
+hipError_t launch_project_route(const void* X, const void* W, int E, void* Qout, int B, int S, int Hq, int Hkv,
+                                const float* proto, int M, int mode, float tau, float* w_out, void* workspace,
+                                hipStream_t s);
 hipError_t launch_route(const void* Q, int B, int S, int Hq, int Hkv, int D, int dtype, const float* proto,
                         int M, int t0, int t1, int mode, float tau, float* w_out, void* workspace,
                         hipStream_t s, const int* lens = nullptr, const int* cu = nullptr, int total = 0,

@@ -193,6 +193,120 @@ __global__ __launch_bounds__(kFinishThreads) void route_finish_kernel(const floa
   }
 }
 
+
+// ---- query projection with the routing sums in its epilogue (Sec. 3.3: the routing query is a by-product of the
+// projection that produces Q, so it need not be read back) ----
+//
+// Q[t, n] = sum_e X[t, e] W[n, e]  (bf16 in, fp32 accumulate, bf16 out; W is the projection weight with one row per
+// output feature, the layout of a linear layer).  One workgroup = 128 tokens x 128 output features (one head at
+// D = 128), four waves of 64 x 64, v_mfma_f32_32x32x16_bf16; 64-wide slices of E go through two LDS stages, the
+// next slice's global loads are in flight while the current one is multiplied.  ROUTE: every wave also sums the
+// rounded outputs of its 64 tokens per feature and writes them as one partial sum of seka_route's first stage, so
+// route_finish_kernel completes the routing without a pass over Q.
+constexpr int kProjTile = 128, kProjK = 64, kProjLd = kProjK + 8;     // LDS row stride in elements (144 bytes: conflict-free 16-byte reads)
+
+template <bool ROUTE>
+__global__ __launch_bounds__(256) void project_route_kernel(const uint16_t* __restrict__ X, const uint16_t* __restrict__ W,
+                                                            uint16_t* __restrict__ Qout, int E, int N, int S, int G,
+                                                            int Hkv, float* __restrict__ workspace) {
+  __shared__ __attribute__((aligned(16))) uint16_t lds[2 * 2 * kProjTile * kProjLd];   // [stage][A | B][128][72]; reused for the output tile
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, hf = lane >> 5;
+  const size_t row0 = (size_t)blockIdx.y * kProjTile;     // first token of the tile (B*S is a multiple of 128)
+  const int col0 = blockIdx.x * kProjTile;                // first output feature
+  // global -> registers: thread t takes 64 contiguous bytes of row t / 2 of both operand tiles
+  const int lrow = tid >> 1, lhalf = tid & 1;
+  const uint16_t* xa = X + (row0 + lrow) * (size_t)E + 32 * lhalf;
+  const uint16_t* wb = W + ((size_t)col0 + lrow) * (size_t)E + 32 * lhalf;
+  uint4 ra[4], rb[4];
+#define SEKA_PROJ_GLOAD(kt)                                                                   \
+  _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                          \
+    ra[i_] = *reinterpret_cast<const uint4*>(xa + (size_t)(kt) * kProjK + 8 * i_);            \
+    rb[i_] = *reinterpret_cast<const uint4*>(wb + (size_t)(kt) * kProjK + 8 * i_);            \
+  }
+#define SEKA_PROJ_LSTORE(stage)                                                               \
+  {                                                                                           \
+    uint16_t* A_ = lds + (stage) * (2 * kProjTile * kProjLd);                                 \
+    uint16_t* B_ = A_ + kProjTile * kProjLd;                                                  \
+    _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                        \
+      *reinterpret_cast<uint4*>(A_ + lrow * kProjLd + 32 * lhalf + 8 * i_) = ra[i_];          \
+      *reinterpret_cast<uint4*>(B_ + lrow * kProjLd + 32 * lhalf + 8 * i_) = rb[i_];          \
+    }                                                                                         \
+  }
+  f32x16 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+  const int nk = E / kProjK;
+  SEKA_PROJ_GLOAD(0)
+  SEKA_PROJ_LSTORE(0)
+  __syncthreads();
+  for (int kt = 0; kt < nk; ++kt) {
+    const int ktn = kt + 1 < nk ? kt + 1 : kt;            // the last turn reloads its own slice (unused)
+    SEKA_PROJ_GLOAD(ktn)
+    const uint16_t* A = lds + (kt & 1) * (2 * kProjTile * kProjLd);
+    const uint16_t* Bm = A + kProjTile * kProjLd;
+#pragma unroll
+    for (int ks = 0; ks < kProjK / 16; ++ks) {
+      bf16x8 a[2], b[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const bf16x8*>(A + (64 * wm + 32 * i + l32) * kProjLd + 16 * ks + 8 * hf);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const bf16x8*>(Bm + (64 * wn + 32 * j + l32) * kProjLd + 16 * ks + 8 * hf);
+      // D[m][n] with m = output feature (operand "A" = W rows) would put tokens on lanes; here tokens are m and
+      // features n, so that a lane owns one feature column and its 16 registers are 16 tokens: the routing sum over
+      // tokens is a sum over registers.
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) SEKA_PROJ_LSTORE((kt + 1) & 1)
+    __syncthreads();
+  }
+#undef SEKA_PROJ_GLOAD
+#undef SEKA_PROJ_LSTORE
+  // ---- epilogue: round, sum for the routing, stage the tile in LDS, store 16 bytes per lane ----
+  constexpr int OLD = kProjTile + 8;                      // output tile row stride in elements
+  uint16_t* Ct = lds;                                     // [128][136] = 34816 B <= the operand stages
+  float colsum[2] = {0.f, 0.f};
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const __bf16 v = (__bf16)acc[i][j][r];
+        colsum[j] += (float)v;
+        const int m = 64 * wm + 32 * i + 8 * (r >> 2) + 4 * hf + (r & 3);
+        Ct[m * OLD + 64 * wn + 32 * j + l32] = __builtin_bit_cast(uint16_t, v);
+      }
+  if (ROUTE) {
+    // this wave's 64 tokens lie in one prompt (S is a multiple of 128); feature column -> (head, d)
+    const size_t tok = row0 + 64 * wm;
+    const int b = (int)(tok / S), tchunk = (int)(tok % S) / 64;
+    const int hq = col0 / 128, h = hq / G, g = hq % G;            // D = 128: one tile column block = one head
+    const int chunks = (S / 64) * G;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const float tot = colsum[j] + __shfl_xor(colsum[j], 32);    // the other 32 tokens of the wave
+      if (hf == 0)
+        workspace[(((size_t)b * Hkv + h) * chunks + (size_t)tchunk * G + g) * 128 + 64 * wn + 32 * j + l32] = tot;
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < (kProjTile * kProjTile / 8) / 256; ++it) {
+    const int idx = tid + 256 * it, m = idx / (kProjTile / 8), c8 = idx % (kProjTile / 8);
+    const uint4 v = *reinterpret_cast<const uint4*>(Ct + m * OLD + 8 * c8);
+    *reinterpret_cast<uint4*>(Qout + (row0 + m) * (size_t)N + col0 + 8 * c8) = v;
+  }
+}
+
 }  // namespace
 
 size_t route_workspace_bytes(int B, int Hkv, int D, int t0, int t1) {
@@ -221,6 +335,31 @@ hipError_t launch_route(const void* Q, int B, int S, int Hq, int Hkv, int D, int
     if (D == 128) SEKA_ROUTE_CASE(float, 128); else SEKA_ROUTE_CASE(float, 64);
   }
 #undef SEKA_ROUTE_CASE
+  return hipGetLastError();
+}
+
+
+size_t project_route_workspace_bytes(int B, int S, int Hq) {
+  return (size_t)B * Hq * (S / 64) * 128 * sizeof(float);
+}
+
+hipError_t launch_project_route(const void* X, const void* W, int E, void* Qout, int B, int S, int Hq, int Hkv,
+                                const float* proto, int M, int mode, float tau, float* w_out, void* workspace,
+                                hipStream_t s) {
+  const int N = Hq * 128, G = Hq / Hkv;
+  const dim3 grid(N / kProjTile, (unsigned)(((size_t)B * S) / kProjTile));
+  float* ws = static_cast<float*>(workspace);
+  if (w_out != nullptr) {
+    hipLaunchKernelGGL((project_route_kernel<true>), grid, dim3(256), 0, s, static_cast<const uint16_t*>(X),
+                       static_cast<const uint16_t*>(W), static_cast<uint16_t*>(Qout), E, N, S, G, Hkv, ws);
+    const float inv_count = 1.0f / ((float)S * (float)G);
+    hipLaunchKernelGGL((route_finish_kernel<128>), dim3(B * Hkv), dim3(kFinishThreads), 0, s, ws, (S / 64) * G, inv_count,
+                       proto, Hkv, M, mode, tau, static_cast<const int*>(nullptr), static_cast<const int*>(nullptr), 0, S, 0, G,
+                       w_out);
+  } else {
+    hipLaunchKernelGGL((project_route_kernel<false>), grid, dim3(256), 0, s, static_cast<const uint16_t*>(X),
+                       static_cast<const uint16_t*>(W), static_cast<uint16_t*>(Qout), E, N, S, G, Hkv, ws);
+  }
   return hipGetLastError();
 }
 

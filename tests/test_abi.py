@@ -23,7 +23,8 @@ def test_exports_every_declared_symbol(B):
             "seka_route_workspace_bytes", "seka_status_string", "seka_set_tuning",
             "seka_attention_decode", "seka_decode_workspace_bytes", "seka_attention_prefill_ragged",
             "seka_learn_workspace_bytes", "seka_learn_projection", "seka_head_distance",
-            "seka_attention_prefill_packed", "seka_route_ragged", "seka_route_ragged_workspace_bytes", "seka_edit_keys_packed"} <= names
+            "seka_attention_prefill_packed", "seka_route_ragged", "seka_route_ragged_workspace_bytes", "seka_edit_keys_packed", "seka_project_route",
+            "seka_project_route_workspace_bytes"} <= names
     for n in names:
         assert hasattr(B.lib, n), f"libseka.so does not export {n}"
 
@@ -136,6 +137,26 @@ def test_route_ragged_rejects_bad_arguments(B):
     assert call(lens=FAKE * 7 + 2) == 4 and call(lens=None, cu=FAKE * 7 + 2, total=10) == 4
     assert call(mode=9) == 6
     assert call(ws=None) == 8 and call(wsb=need - 1) == 8
+
+
+def test_project_route_rejects_bad_arguments(B):
+    L = B.lib
+    ok = _shape(B, S=256, Hq=8, Hkv=2, D=128, dtype=B.SEKA_BF16)
+    need = L.seka_project_route_workspace_bytes(ctypes.byref(ok))
+    assert need > 0 and need % 16 == 0
+    assert L.seka_project_route_workspace_bytes(ctypes.byref(_shape(B, S=200, Hq=8, Hkv=2, D=128, dtype=B.SEKA_BF16))) == 0
+    far = FAKE * 4096
+    call = lambda **kw: L.seka_project_route(kw.get("X", FAKE), kw.get("W", FAKE * 64), kw.get("E", 256), kw.get("Q", far),
+                                             ctypes.byref(kw.get("sh", ok)), kw.get("proto", FAKE * 2), kw.get("M", 4), kw.get("mode", 0),
+                                             kw.get("tau", 10.0), kw.get("w", FAKE * 3), kw.get("ws", FAKE * 5), kw.get("wsb", need), None)
+    assert call(X=None) == 1 and call(Q=None) == 1 and call(proto=None) == 1
+    assert call(E=100) == 2 and call(E=0) == 2 and call(M=0) == 2
+    assert call(sh=_shape(B, S=200, Hq=8, Hkv=2, D=128, dtype=B.SEKA_BF16)) == 6      # S not a multiple of 128
+    assert call(sh=_shape(B, S=256, Hq=8, Hkv=2, D=64, dtype=B.SEKA_BF16)) == 6       # D = 64
+    assert call(sh=_shape(B, S=256, Hq=8, Hkv=2, D=128)) == 6                          # fp32
+    assert call(Q=FAKE) == 5                                                           # output over the input
+    assert call(ws=None) == 8 and call(wsb=need - 1) == 8
+    assert call(mode=9) == 6
 
 
 def test_tuning_rejects_unknown(B):

@@ -88,3 +88,22 @@ def test_mean_group_query_last_token():
     qb = orc.mean_group_query(Q, 3, 4, 5)
     for h in range(3):
         np.testing.assert_allclose(qb[:, h], Q[:, 4, 2 * h:2 * h + 2].mean(1), atol=1e-15)
+
+
+def test_project_queries_pins():
+    """The projection against what fixes it: identity weights return the input, a one-hot weight row picks one
+    input feature, and a tiny case agrees with sums written out term by term."""
+    g = np.random.default_rng(3)
+    B, T, Hq, D = 2, 5, 3, 4
+    E = Hq * D
+    X = g.standard_normal((B, T, E))
+    assert np.array_equal(orc.project_queries(X, np.eye(E), Hq), X.reshape(B, T, Hq, D))
+    W = np.zeros((E, E)); W[7, 2] = 3.0                     # output feature 7 = head 1, d 3 reads input feature 2
+    Q = orc.project_queries(X, W, Hq)
+    assert np.array_equal(Q[:, :, 1, 3], 3.0 * X[:, :, 2]) and np.count_nonzero(Q) == B * T
+    W = g.standard_normal((E, 6)); X6 = g.standard_normal((1, 2, 6))
+    Q = orc.project_queries(X6, W, Hq)
+    for t_ in range(2):
+        for n in range(E):
+            want = sum(X6[0, t_, e] * W[n, e] for e in range(6))
+            assert abs(Q[0, t_, n // D, n % D] - want) < 1e-12

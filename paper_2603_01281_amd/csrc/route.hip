@@ -219,19 +219,41 @@ __global__ __launch_bounds__(256) void project_route_kernel(const uint16_t* __re
   const int lrow = tid >> 1, lhalf = tid & 1;
   const uint16_t* xa = X + (row0 + lrow) * (size_t)E + 32 * lhalf;
   const uint16_t* wb = W + ((size_t)col0 + lrow) * (size_t)E + 32 * lhalf;
-  uint4 ra[4], rb[4];
-#define SEKA_PROJ_GLOAD(kt)                                                                   \
-  _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                          \
-    ra[i_] = *reinterpret_cast<const uint4*>(xa + (size_t)(kt) * kProjK + 8 * i_);            \
-    rb[i_] = *reinterpret_cast<const uint4*>(wb + (size_t)(kt) * kProjK + 8 * i_);            \
-  }
-#define SEKA_PROJ_LSTORE(stage)                                                               \
+  // Two register sets: a slice is requested two turns before it is multiplied (one turn in flight, written to
+  // LDS at the end of the next), so a turn of 16 MFMAs per wave does not have to cover the whole memory latency.
+  typedef unsigned int proj_u32x4 __attribute__((ext_vector_type(4)));
+  struct Slice { proj_u32x4 a0, a1, a2, a3, b0, b1, b2, b3; };
+  Slice r0, r1;
+#define SEKA_PROJ_GLOAD(r, kt)                                                                \
   {                                                                                           \
-    uint16_t* A_ = lds + (stage) * (2 * kProjTile * kProjLd);                                 \
-    uint16_t* B_ = A_ + kProjTile * kProjLd;                                                  \
-    _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                        \
-      *reinterpret_cast<uint4*>(A_ + lrow * kProjLd + 32 * lhalf + 8 * i_) = ra[i_];          \
-      *reinterpret_cast<uint4*>(B_ + lrow * kProjLd + 32 * lhalf + 8 * i_) = rb[i_];          \
+    const int kt_ = (kt) < nk ? (kt) : nk - 1;            /* past the end: a slice nobody uses */ \
+    const proj_u32x4* pa_ = reinterpret_cast<const proj_u32x4*>(xa + (size_t)kt_ * kProjK);   \
+    const proj_u32x4* pb_ = reinterpret_cast<const proj_u32x4*>(wb + (size_t)kt_ * kProjK);   \
+    r.a0 = pa_[0]; r.a1 = pa_[1]; r.a2 = pa_[2]; r.a3 = pa_[3];                               \
+    r.b0 = pb_[0]; r.b1 = pb_[1]; r.b2 = pb_[2]; r.b3 = pb_[3];                               \
+  }
+#define SEKA_PROJ_LSTORE(r, stage)                                                            \
+  {                                                                                           \
+    proj_u32x4* A_ = reinterpret_cast<proj_u32x4*>(lds + (stage) * (2 * kProjTile * kProjLd) + lrow * kProjLd + 32 * lhalf); \
+    proj_u32x4* B_ = reinterpret_cast<proj_u32x4*>(lds + (stage) * (2 * kProjTile * kProjLd) + kProjTile * kProjLd + lrow * kProjLd + 32 * lhalf); \
+    A_[0] = r.a0; A_[1] = r.a1; A_[2] = r.a2; A_[3] = r.a3;                                   \
+    B_[0] = r.b0; B_[1] = r.b1; B_[2] = r.b2; B_[3] = r.b3;                                   \
+  }
+  // Tokens are the MFMA's rows and features its columns, so that a lane owns one feature column and its 16
+  // registers are 16 tokens: the routing sum over tokens is a sum over registers.
+#define SEKA_PROJ_COMPUTE(stage)                                                              \
+  {                                                                                           \
+    const uint16_t* A_ = lds + (stage) * (2 * kProjTile * kProjLd);                           \
+    const uint16_t* B_ = A_ + kProjTile * kProjLd;                                            \
+    _Pragma("unroll") for (int ks = 0; ks < kProjK / 16; ++ks) {                              \
+      bf16x8 a_[2], b_[2];                                                                    \
+      _Pragma("unroll") for (int i = 0; i < 2; ++i)                                           \
+        a_[i] = *reinterpret_cast<const bf16x8*>(A_ + (64 * wm + 32 * i + l32) * kProjLd + 16 * ks + 8 * hf); \
+      _Pragma("unroll") for (int j = 0; j < 2; ++j)                                           \
+        b_[j] = *reinterpret_cast<const bf16x8*>(B_ + (64 * wn + 32 * j + l32) * kProjLd + 16 * ks + 8 * hf); \
+      _Pragma("unroll") for (int i = 0; i < 2; ++i)                                           \
+        _Pragma("unroll") for (int j = 0; j < 2; ++j)                                         \
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_[i], b_[j], acc[i][j], 0, 0, 0); \
     }                                                                                         \
   }
   f32x16 acc[2][2];
@@ -242,34 +264,28 @@ __global__ __launch_bounds__(256) void project_route_kernel(const uint16_t* __re
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
   const int nk = E / kProjK;
-  SEKA_PROJ_GLOAD(0)
-  SEKA_PROJ_LSTORE(0)
+  SEKA_PROJ_GLOAD(r0, 0)
+  SEKA_PROJ_LSTORE(r0, 0)
   __syncthreads();
-  for (int kt = 0; kt < nk; ++kt) {
-    const int ktn = kt + 1 < nk ? kt + 1 : kt;            // the last turn reloads its own slice (unused)
-    SEKA_PROJ_GLOAD(ktn)
-    const uint16_t* A = lds + (kt & 1) * (2 * kProjTile * kProjLd);
-    const uint16_t* Bm = A + kProjTile * kProjLd;
-#pragma unroll
-    for (int ks = 0; ks < kProjK / 16; ++ks) {
-      bf16x8 a[2], b[2];
-#pragma unroll
-      for (int i = 0; i < 2; ++i) a[i] = *reinterpret_cast<const bf16x8*>(A + (64 * wm + 32 * i + l32) * kProjLd + 16 * ks + 8 * hf);
-#pragma unroll
-      for (int j = 0; j < 2; ++j) b[j] = *reinterpret_cast<const bf16x8*>(Bm + (64 * wn + 32 * j + l32) * kProjLd + 16 * ks + 8 * hf);
-      // D[m][n] with m = output feature (operand "A" = W rows) would put tokens on lanes; here tokens are m and
-      // features n, so that a lane owns one feature column and its 16 registers are 16 tokens: the routing sum over
-      // tokens is a sum over registers.
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
-    if (kt + 1 < nk) SEKA_PROJ_LSTORE((kt + 1) & 1)
+  SEKA_PROJ_GLOAD(r0, 1)
+  int kt = 0;
+  for (; kt + 1 < nk; kt += 2) {
+    // even turn: stage 0 holds slice kt, set 0 holds slice kt + 1
+    SEKA_PROJ_GLOAD(r1, kt + 2)
+    SEKA_PROJ_COMPUTE(0)
+    SEKA_PROJ_LSTORE(r0, 1)
+    __syncthreads();
+    // odd turn: stage 1 holds slice kt + 1, set 1 holds slice kt + 2 (past the end: a copy of the last slice)
+    SEKA_PROJ_GLOAD(r0, kt + 3)
+    SEKA_PROJ_COMPUTE(1)
+    SEKA_PROJ_LSTORE(r1, 0)
     __syncthreads();
   }
+  if (kt < nk) SEKA_PROJ_COMPUTE(0)                        // an odd number of slices: the last one sits in stage 0
+  __syncthreads();
 #undef SEKA_PROJ_GLOAD
 #undef SEKA_PROJ_LSTORE
+#undef SEKA_PROJ_COMPUTE
   // ---- epilogue: round, sum for the routing, stage the tile in LDS, store 16 bytes per lane ----
   constexpr int OLD = kProjTile + 8;                      // output tile row stride in elements
   uint16_t* Ct = lds;                                     // [128][136] = 34816 B <= the operand stages

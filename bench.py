@@ -23,11 +23,20 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
 
-# HBM bytes of one fused steered launch at this workload, from hardware counters (rocprofv3 --pmc FETCH_SIZE and
-# --pmc WRITE_SIZE runs of this script, each scaled by what the same counter reads for a 256 MiB device copy:
-# x2.0 for FETCH_SIZE, x1.0 for WRITE_SIZE; summary in profiles/attention_bf16_cfg3_hbm_traffic.md).
-# Algorithmic bytes are Q + K + V + O = 671 MB; the rest is K/V re-fetched by workgroups on different XCDs.
-MEASURED_TRAFFIC_BYTES = {"fetch": 289345.6 * 1024 * 2.0, "write": 262144.0 * 1024 * 1.0}
+TRAFFIC_JSON = os.path.join(ROOT, "profiles", "attention_bf16_cfg3_hbm_traffic.json")
+
+
+def measured_traffic_bytes():
+    """HBM bytes of one fused steered launch at this workload, from hardware counters: two rocprofv3 --pmc runs of
+    this script (FETCH_SIZE, then WRITE_SIZE, KiB per dispatch), each scaled by what the same counter reads for a
+    256 MiB device copy in the same run.  The figures are kept next to their summary under profiles/ and read from
+    there; None if the file is missing.  (Algorithmic bytes are Q + K + V + O = 671 MB; the rest is K/V fetched
+    again by workgroups on other XCDs.)"""
+    try:
+        t = json.load(open(TRAFFIC_JSON))
+        return round(1024.0 * (t["fetch_size_kib"] * t["fetch_scale"] + t["write_size_kib"] * t["write_scale"]))
+    except (OSError, KeyError, ValueError):
+        return None
 
 
 def parse():
@@ -63,7 +72,7 @@ def build_stack(torch, inputs, L, seed=0):
         K = torch.randn((B, S, Hkv, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
         V = torch.randn((B, S, Hkv, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
         O = torch.empty_like(Q)
-        item = dict(Q=Q, K=K, V=V, O=O, gain=float(gains[l]))
+        item = dict(Q=Q, K=K, V=V, O=O, gain=float(gains[l]), layer=l)
         if gains[l] != 0:
             U = inputs.orthonormal_bases(Hkv, 1, D, r, seed, "bf16", layer=l)
             mask, spans = inputs.span_mask(B, S, seed, ("cover", 0.05, 0.20, 4), layer=l)
@@ -81,9 +90,11 @@ def run_layer(seka, it, Hkv):
         seka.seka_attention_plain(it["Q"], it["K"], it["V"], it["O"])
 
 
-def cpu_baseline(inputs):
-    """The fp64 oracle, unmodified, on a bounded sample of the same workload: layer 8 (the first steered layer),
-    batch entry 0 (all 8 KV heads, 32 query heads), all 8192 tokens."""
+def cpu_baseline_and_parity(torch, inputs, item, Hkv):
+    """The fp64 oracle, unmodified, on a bounded sample of the timed workload: batch entry 0 of the first steered
+    layer (all 8 KV heads, 32 query heads, all 8192 tokens), run on the bytes of the tensors the timed launches
+    read.  Its run time is the CPU baseline; its result is compared with what the last timed launch of that layer
+    left in O, which ties the timed launches to a checked result."""
     import numpy as np
     from oracle import seka_oracle as orc
     try:
@@ -91,18 +102,23 @@ def cpu_baseline(inputs):
         threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         threads = os.cpu_count() or 1
-    shp = inputs.CONFIG_SHAPES[3]
-    S, D, G = shp["S"], shp["D"], shp["Hq"] // shp["Hkv"]
-    inp = inputs.make_layer("cfg3-sample", "bf16", B=1, S=S, Hq=shp["Hq"], Hkv=shp["Hkv"], D=D, M=1, r=shp["r"],
-                            gain=float(inputs.layer_gains_cfg3(0)[8]), mask_recipe=("cover", 0.05, 0.20, 4), seed=0, layer=8)
-    Q, K, V, U = inp.widen(inp.Q), inp.widen(inp.K), inp.widen(inp.V), inp.widen(inp.U)
+    f64 = lambda t: t.float().cpu().numpy().astype(np.float64)
+    Q, K, V, U = f64(item["Q"][:1]), f64(item["K"][:1]), f64(item["V"][:1]), f64(item["U"])
+    mask = item["mask"][:1].cpu().numpy()
+    got = f64(item["O"][:1])
+    S, Hq, D = Q.shape[1], Q.shape[2], Q.shape[3]
     t0 = time.perf_counter()
-    orc.steered_attention(Q, K, V, U, inp.gain, inp.mask, scale=inp.scale)
+    ref, _ = orc.steered_attention(Q, K, V, U, [item["gain"]] * Hkv, mask)
     dt = time.perf_counter() - t0
-    fl = attn_flops(1, S, shp["Hq"], D)
-    return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle", "seconds": round(dt, 2),
-            "sample": "cfg3 layer 8, batch entry 0 (8 KV heads, 32 query heads), all 8192 tokens "
-                      "(1/4 of one layer, 1/128 of a step); same causal-pair flop convention"}
+    fl = attn_flops(1, S, Hq, D)
+    sample = (f"cfg3 layer {item['layer']}, batch entry 0 (8 KV heads, 32 query heads), all {S} tokens "
+              "(1/4 of one layer, 1/128 of a step); same causal-pair flop convention")
+    d = np.abs(got - ref)
+    base = {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": int(threads), "kind": "oracle", "seconds": round(dt, 2), "sample": sample}
+    parity = {"max_abs_diff": float(d.max()), "mean_abs_diff": float(d.mean()), "tolerance": {"max": 2e-2, "mean": 2e-3},
+              "ok": bool(np.isfinite(got).all() and d.max() <= 2e-2 and d.mean() <= 2e-3),
+              "sample": f"O of the last timed launch of layer {item['layer']}, batch entry 0, every row of every head, against the fp64 oracle on the same tensors"}
+    return base, parity
 
 
 def time_config(torch, seka, inputs, cfg, iters=10):
@@ -174,6 +190,56 @@ def time_config(torch, seka, inputs, cfg, iters=10):
     return out
 
 
+def time_stress_masks(torch, seka, inputs):
+    """Highlight-coverage stress cases at configuration 2's shape (not graded): nothing highlighted (pure dispatch
+    overhead of the steered kernel), about 70 % of the tokens in one contiguous block (a long middle passage
+    highlighted, the paper's lost-in-the-middle use), and everything."""
+    import numpy as np
+    shp = inputs.CONFIG_SHAPES[2]
+    B, S, Hq, Hkv, D, r = (shp[k] for k in ("B", "S", "Hq", "Hkv", "D", "r"))
+    gen = torch.Generator(device="cuda"); gen.manual_seed(22)
+    mk = lambda h: torch.randn((B, S, h, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    Q, K, V = mk(Hq), mk(Hkv), mk(Hkv)
+    O = torch.empty_like(Q)
+    U = torch.from_numpy(inputs.orthonormal_bases(Hkv, 1, D, r, 0, "bf16").view(np.int16)).view(torch.bfloat16).cuda()
+    fl = attn_flops(B, S, Hq, D)
+    out = {}
+    for name, lo, hi in (("0pct", 0, 0), ("70pct_contiguous", int(0.15 * S), int(0.85 * S)), ("100pct", 0, S)):
+        m = np.zeros((B, S), np.uint8)
+        m[:, lo:hi] = 1
+        mask = torch.from_numpy(m).cuda()
+        plain, steer = paired_medians(torch, lambda: seka.seka_attention_plain(Q, K, V, O),
+                                      lambda: seka.seka_attention_prefill(Q, K, V, O, U, [1.0] * Hkv, mask), fl)
+        out[name] = {"coverage": round(float(m.mean()), 3), "plain_ms": round(plain, 4), "steered_ms": round(steer, 4),
+                     "overhead_pct": round(100 * (steer / plain - 1), 2)}
+    return out
+
+
+def time_stacked_edit(torch, seka, inputs, layers=16, iters=10):
+    """Steady-state bandwidth of the standalone key edit: the keys of 16 layers of configuration 3 in one launch
+    (the layer index treated as extra batch: 64 x 8192 tokens x 8 KV heads x 128, 1.07 GB read and 1.07 GB written
+    out of place), a working set eight times the 256 MB last-level cache, so the figure is HBM traffic and not a
+    cache hit rate.  In place, only the highlighted rows move."""
+    import numpy as np
+    shp = inputs.CONFIG_SHAPES[3]
+    B, S, Hkv, D, r = shp["B"] * layers, shp["S"], shp["Hkv"], shp["D"], shp["r"]
+    gen = torch.Generator(device="cuda"); gen.manual_seed(33)
+    K = torch.randn((B, S, Hkv, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    K2 = torch.empty_like(K)
+    U = torch.from_numpy(inputs.orthonormal_bases(Hkv, 1, D, r, 0, "bf16").view(np.int16)).view(torch.bfloat16).cuda()
+    m = np.concatenate([inputs.span_mask(shp["B"], S, 0, ("cover", 0.05, 0.20, 4), layer=8 + l)[0] for l in range(layers)])
+    mask = torch.from_numpy(m).cuda()
+    gain = [1.0] * Hkv
+    oop = event_time(torch, lambda: seka.seka_edit_keys(K, K2, U, gain, mask), iters, warm=3)
+    inp = event_time(torch, lambda: seka.seka_edit_keys(K2, K2, U, [1e-3] * Hkv, mask), iters, warm=3)
+    nbytes = K.numel() * 2
+    hl_bytes = float(m.sum()) * Hkv * D * 2
+    return {"layers": layers, "tokens": B * S, "coverage": round(float(m.mean()), 3),
+            "out_of_place_ms": round(oop, 4), "out_of_place_GBps": round((2 * nbytes + m.size) / oop / 1e6, 1),
+            "in_place_ms": round(inp, 4), "in_place_GBps": round((2 * hl_bytes + m.size) / inp / 1e6, 1),
+            "algorithmic_bytes_out_of_place": 2 * nbytes + m.size, "algorithmic_bytes_in_place": int(2 * hl_bytes + m.size)}
+
+
 def time_learn(torch, seka, inputs, n=16384, Hkv=8, D=128, iters=5):
     """Offline stage for one layer of configuration 3's shape: n paired sample tokens per KV head."""
     import numpy as np
@@ -196,7 +262,7 @@ def mfma_only_rate(torch):
     """What a loop of bf16 MFMAs alone sustains on this device with constant and with random operands (a stand-alone
     probe built next to the library): context for the roofline fraction, which is quoted against the published peak."""
     import subprocess
-    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "paper_2603_01281_amd", "mfma_rate_probe.bin")
+    exe = os.path.join(ROOT, "mfma_rate_probe.bin")
     if not os.path.exists(exe):
         return None
     torch.cuda.synchronize()
@@ -294,8 +360,8 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "attention_bf16_pipe_kernel<4 heads x 64 rows, steered, rank <= 32> (seka_attention_prefill)",
                      "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                     "traffic": round(sum(MEASURED_TRAFFIC_BYTES.values())) if L == 32 and B == 4 and S == 8192 else None,
-                     "traffic_unit": "bytes per launch (offline counter runs, see profiles/)",
+                     "traffic": measured_traffic_bytes() if B == 4 and S == 8192 else None,
+                     "traffic_unit": "bytes per launch (rocprofv3 counter runs of this script, kept under profiles/)",
                      "algorithmic_bytes": 2 * (2 * B * S * Hq * D + 2 * B * S * Hkv * D),
                      "flops_per_launch": fl_layer, "launch_ms": round(st_ms, 4)},
     }
@@ -308,14 +374,22 @@ def main():
     if args.extras:
         out["other_configs"] = {f"cfg{c}": time_config(torch, seka, inputs, c) for c in (2, 3, 4, 5)}
         out["offline_learn"] = time_learn(torch, seka, inputs)
+        out["stress_masks_cfg2"] = time_stress_masks(torch, seka, inputs)
+    sample_item = None
+    if steered_ix and not args.no_cpu_baseline:                 # keep (on the host) what the parity check needs
+        it = layers[steered_ix[0]]
+        sample_item = {k: (v[:1].cpu() if k in ("Q", "K", "V", "O", "mask") else v.cpu() if k == "U" else v) for k, v in it.items()}
     del layers
     torch.cuda.empty_cache()
+    if args.extras:
+        out["edit_keys_16_layers"] = time_stacked_edit(torch, seka, inputs)      # 2.1 GB: after the stack is freed
+        torch.cuda.empty_cache()
     try:
         out["mfma_only_rate"] = mfma_only_rate(torch)        # about a second; context for roofline.frac
     except Exception as e:                                   # the probe is optional: never fail the measurement over it
         out["mfma_only_rate"] = {"error": str(e)[-200:]}
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(inputs)
+    if not args.no_cpu_baseline and steered_ix:
+        out["cpu_baseline"], out["parity"] = cpu_baseline_and_parity(torch, inputs, sample_item, Hkv)
     print(json.dumps(out))
 
 

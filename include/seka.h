@@ -15,6 +15,9 @@
  *     enqueue kernels on `hip_stream` (a hipStream_t passed as void*; NULL = the default
  *     stream) and return without waiting.  The library never allocates or frees device memory.
  *   - Inputs are never written.  Outputs must not overlap inputs unless stated.
+ *   - Size limits beyond those stated per call (SEKA_ERR_SHAPE): S * H * D < 2^31 elements per prompt;
+ *     B * Hkv <= 65535 for the routing calls, B <= 65535 for the edit and decode calls, B * S / 128 <= 65535
+ *     for seka_project_route (their launch grids carry these on an axis that HIP limits to 65535).
  *   - Return value: SEKA_OK or an error code; seka_status_string() names it.
  */
 #ifndef SEKA_H
@@ -273,13 +276,6 @@ const char* seka_status_string(int32_t status);
 /* HIP runtime's description of the calling thread's most recent launch result ("no error" after a
  * success); for diagnosing SEKA_ERR_LAUNCH.  Static storage, never NULL. */
 const char* seka_last_launch_error(void);
-
-/*
- * seka_set_tuning — select among kernel variants that compute the same result (for benchmarks).
- * key 0: bf16 attention variant id (0 = library default).  Unknown keys/values return
- * SEKA_ERR_UNSUPPORTED and change nothing.  Not thread-safe with concurrent launches.
- */
-seka_status seka_set_tuning(int32_t key, int32_t value);
 
 #ifdef __cplusplus
 }

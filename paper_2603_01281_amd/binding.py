@@ -45,8 +45,6 @@ lib.seka_status_string.restype = ctypes.c_char_p
 lib.seka_status_string.argtypes = [_i32]
 lib.seka_last_launch_error.restype = ctypes.c_char_p
 lib.seka_last_launch_error.argtypes = []
-lib.seka_set_tuning.restype = _i32
-lib.seka_set_tuning.argtypes = [_i32, _i32]
 lib.seka_route_workspace_bytes.restype = _sz
 lib.seka_route_workspace_bytes.argtypes = [_shape_p, _i32, _i32]
 lib.seka_route.restype = _i32
@@ -126,11 +124,27 @@ def _shape(B, S, Hq, Hkv, D, dtype, scale):
     return seka_shape(B, S, Hq, Hkv, D, dtype, float(scale))
 
 
-def _steer(U, gain, mask, w, Hkv, key_scale=None):
-    """U [Hkv,M,D,r] device tensor; gain: host sequence of Hkv floats; mask [B,S] uint8 device; w [B,Hkv,M] fp32
-    device or None; key_scale: host sequence of Hkv floats or None (all ones)."""
+def _steer(U, gain, mask, w, Hkv, key_scale=None, tokens=None, D=None, dtype=None, B=None):
+    """U [Hkv,M,D,r] device tensor; gain: host sequence of Hkv floats; mask [B,S] (or [total]) uint8 device; w [B,Hkv,M]
+    fp32 device or None; key_scale: host sequence of Hkv floats or None (all ones).  tokens: the number of mask
+    bytes the call will index; D, dtype, B: what U, mask and w must agree with."""
+    torch = _torch()
     if U.dim() != 4:
         raise ValueError("U must be [Hkv, M, D, r]")
+    if U.shape[0] != Hkv or (D is not None and U.shape[2] != D):
+        raise ValueError(f"U is {tuple(U.shape)}, expected [Hkv={Hkv}, M, D={D}, r]")
+    if dtype is not None and U.dtype != dtype:
+        raise TypeError(f"U must have the tensors' dtype {dtype}, got {U.dtype}")
+    if mask is None or mask.dtype != torch.uint8:
+        raise TypeError("mask must be a uint8 tensor")
+    if tokens is not None and mask.numel() != tokens:
+        raise ValueError(f"mask has {mask.numel()} entries, expected one per token ({tokens})")
+    if len(gain) != Hkv or (key_scale is not None and len(key_scale) != Hkv):
+        raise ValueError(f"gain / key_scale must have one entry per KV head ({Hkv})")
+    if w is not None:
+        if w.dtype != torch.float32 or w.dim() != 3 or w.shape[1] != Hkv or w.shape[2] != U.shape[1] or \
+                (B is not None and w.shape[0] != B):
+            raise ValueError(f"w must be fp32 [B={B}, Hkv={Hkv}, M={U.shape[1]}], got {w.dtype} {tuple(w.shape)}")
     gains = (ctypes.c_float * Hkv)(*[float(g) for g in gain])
     scales = None
     if key_scale is not None:
@@ -138,10 +152,6 @@ def _steer(U, gain, mask, w, Hkv, key_scale=None):
     st = seka_steer(int(U.shape[1]), int(U.shape[3]), _dev(U, "U"), _dev(w, "w"), gains, _dev(mask, "mask"), scales)
     st._keepalive = (gains, scales)
     return st
-
-
-def seka_set_tuning(key, value):
-    _check(lib.seka_set_tuning(key, value))
 
 
 def seka_route_workspace_bytes(B, S, Hq, Hkv, D, dtype, t0, t1):
@@ -223,7 +233,7 @@ def seka_edit_keys(K_in, K_out, U, gain, mask, w=None, stream=None, key_scale=No
     """K_in/K_out [B,S,Hkv,D]; K_out may be K_in itself (in place)."""
     B, S, Hkv, D = K_in.shape
     sh = _shape(B, S, Hkv, Hkv, D, _dtype_code(K_in), 0.0)
-    st = _steer(U, gain, mask, w, Hkv, key_scale)
+    st = _steer(U, gain, mask, w, Hkv, key_scale, tokens=B * S, D=D, dtype=K_in.dtype, B=B)
     _check(lib.seka_edit_keys(_dev(K_in, "K_in"), _dev(K_out, "K_out"), ctypes.byref(sh), ctypes.byref(st), _stream(stream)))
     return K_out
 
@@ -233,7 +243,7 @@ def seka_edit_keys_packed(K_in, K_out, cu_seqlens, max_len, U, gain, mask, w=Non
     total, Hkv, D = K_in.shape
     B = cu_seqlens.numel() - 1
     sh = _shape(B, max_len, Hkv, Hkv, D, _dtype_code(K_in), 0.0)
-    st = _steer(U, gain, mask, w, Hkv, key_scale)
+    st = _steer(U, gain, mask, w, Hkv, key_scale, tokens=total, D=D, dtype=K_in.dtype, B=B)
     _check(lib.seka_edit_keys_packed(_dev(K_in, "K_in"), _dev(K_out, "K_out"), ctypes.byref(sh), ctypes.byref(st),
                                      _dev(cu_seqlens, "cu_seqlens"), total, _stream(stream)))
     return K_out
@@ -243,7 +253,7 @@ def seka_attention_prefill(Q, K, V, O, U, gain, mask, w=None, lse=None, scale=0.
     B, S, Hq, D = Q.shape
     Hkv = K.shape[2]
     sh = _shape(B, S, Hq, Hkv, D, _dtype_code(Q), scale)
-    st = _steer(U, gain, mask, w, Hkv, key_scale)
+    st = _steer(U, gain, mask, w, Hkv, key_scale, tokens=B * S, D=D, dtype=Q.dtype, B=B)
     _check(lib.seka_attention_prefill(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(O, "O"), _dev(lse, "lse"),
                                       ctypes.byref(sh), ctypes.byref(st), _stream(stream)))
     return O
@@ -289,7 +299,7 @@ def seka_attention_prefill_ragged(Q, K, V, O, seq_lens, U=None, gain=None, mask=
     B, S, Hq, D = Q.shape
     Hkv = K.shape[2]
     sh = _shape(B, S, Hq, Hkv, D, _dtype_code(Q), scale)
-    st = ctypes.byref(_steer(U, gain, mask, w, Hkv, key_scale)) if U is not None else None
+    st = ctypes.byref(_steer(U, gain, mask, w, Hkv, key_scale, tokens=B * S, D=D, dtype=Q.dtype, B=B)) if U is not None else None
     _check(lib.seka_attention_prefill_ragged(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(O, "O"), _dev(lse, "lse"),
                                              ctypes.byref(sh), st, _dev(seq_lens, "seq_lens"), _stream(stream)))
     return O
@@ -335,7 +345,7 @@ def seka_attention_prefill_packed(Q, K, V, O, cu_seqlens, max_len, U=None, gain=
     Hkv = K.shape[1]
     B = cu_seqlens.numel() - 1
     sh = _shape(B, max_len, Hq, Hkv, D, _dtype_code(Q), scale)
-    st = ctypes.byref(_steer(U, gain, mask, w, Hkv, key_scale)) if U is not None else None
+    st = ctypes.byref(_steer(U, gain, mask, w, Hkv, key_scale, tokens=total, D=D, dtype=Q.dtype, B=B)) if U is not None else None
     _check(lib.seka_attention_prefill_packed(_dev(Q, "Q"), _dev(K, "K"), _dev(V, "V"), _dev(O, "O"), _dev(lse, "lse"),
                                              ctypes.byref(sh), st, _dev(cu_seqlens, "cu_seqlens"), total,
                                              _stream(stream)))

@@ -7,7 +7,6 @@
 
 namespace {
 
-int g_attn_bf16_variant = 0;
 thread_local hipError_t g_last_hip_error = hipSuccess;
 
 seka_status launch_status(hipError_t e) {
@@ -19,6 +18,9 @@ seka_status launch_status(hipError_t e) {
 inline bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 inline size_t elem_size(int dtype) { return dtype == SEKA_BF16 ? 2 : 4; }
+
+// Launch grids put the batch (or batch x KV heads) on the y or z axis, which HIP limits to 65535 workgroups.
+constexpr int64_t kMaxGridYZ = 65535;
 
 seka_status check_shape(const seka_shape* sh, bool need_q_heads) {
   if (!sh) return SEKA_ERR_NULL;
@@ -101,7 +103,7 @@ seka_status attention_common(const void* Q, const void* K, const void* V, void* 
   hipStream_t stream = reinterpret_cast<hipStream_t>(hip_stream);
   (void)hipGetLastError();   // drop any stale error left by earlier, unrelated runtime calls of this thread
   hipError_t e = (sh->dtype == SEKA_BF16)
-                     ? seka::launch_attention_bf16(a, steered ? &sa : nullptr, g_attn_bf16_variant, stream)
+                     ? seka::launch_attention_bf16(a, steered ? &sa : nullptr, stream)
                      : seka::launch_attention_f32(a, steered ? &sa : nullptr, stream);
   return launch_status(e);
 }
@@ -127,14 +129,6 @@ const char* seka_status_string(int32_t status) {
 
 const char* seka_last_launch_error(void) { return hipGetErrorString(g_last_hip_error); }
 
-seka_status seka_set_tuning(int32_t key, int32_t value) {
-  if (key == 0 && seka::attention_bf16_variant_ok(value)) {
-    g_attn_bf16_variant = value;
-    return SEKA_OK;
-  }
-  return SEKA_ERR_UNSUPPORTED;
-}
-
 size_t seka_route_workspace_bytes(const seka_shape* sh, int32_t t0, int32_t t1) {
   if (check_shape(sh, true) != SEKA_OK || t0 < 0 || t1 <= t0 || t1 > sh->S) return 0;
   return seka::route_workspace_bytes(sh->B, sh->Hkv, sh->D, t0, t1);
@@ -148,6 +142,7 @@ seka_status seka_route(const void* Q, const seka_shape* sh, const float* proto, 
   if (!Q || !proto || !w_out) return SEKA_ERR_NULL;
   if (M < 1 || M > SEKA_MAX_EXPERTS) return SEKA_ERR_SHAPE;
   if (t0 < 0 || t1 <= t0 || t1 > sh->S) return SEKA_ERR_SHAPE;
+  if ((int64_t)sh->B * sh->Hkv > kMaxGridYZ) return SEKA_ERR_SHAPE;
   if (mode != SEKA_ROUTE_SOFTMAX_COS && mode != SEKA_ROUTE_PAPER_EQ6) return SEKA_ERR_UNSUPPORTED;
   if (!std::isfinite(tau)) return SEKA_ERR_SHAPE;
   if (misaligned(Q) || misaligned(proto) || (reinterpret_cast<uintptr_t>(w_out) & 3u)) return SEKA_ERR_ALIGN;
@@ -174,6 +169,7 @@ seka_status seka_route_ragged(const void* Q, const seka_shape* sh, const float* 
   if (!Q || !proto || !w_out) return SEKA_ERR_NULL;
   if (!seq_lens && !cu_seqlens) return SEKA_ERR_NULL;
   if (M < 1 || M > SEKA_MAX_EXPERTS || window < 1) return SEKA_ERR_SHAPE;
+  if ((int64_t)sh->B * sh->Hkv > kMaxGridYZ) return SEKA_ERR_SHAPE;
   if (cu_seqlens && (total_tokens < 1 || total_tokens > 0x7fffffffLL)) return SEKA_ERR_SHAPE;
   if (mode != SEKA_ROUTE_SOFTMAX_COS && mode != SEKA_ROUTE_PAPER_EQ6) return SEKA_ERR_UNSUPPORTED;
   if (!std::isfinite(tau)) return SEKA_ERR_SHAPE;
@@ -202,6 +198,7 @@ seka_status seka_project_route(const void* X, const void* Wq, int32_t E, void* Q
   if (rc != SEKA_OK) return rc;
   if (!X || !Wq || !Q_out) return SEKA_ERR_NULL;
   if (E < 64 || E % 64 != 0) return SEKA_ERR_SHAPE;
+  if ((int64_t)sh->B * sh->S / 128 > kMaxGridYZ || (int64_t)sh->B * sh->Hkv > kMaxGridYZ) return SEKA_ERR_SHAPE;
   if (sh->dtype != SEKA_BF16 || sh->D != 128 || sh->S % 128 != 0) return SEKA_ERR_UNSUPPORTED;
   if ((int64_t)sh->Hq * sh->D * (int64_t)E >= ((int64_t)1 << 40)) return SEKA_ERR_SHAPE;
   if (misaligned(X) || misaligned(Wq) || misaligned(Q_out)) return SEKA_ERR_ALIGN;
@@ -229,6 +226,7 @@ seka_status seka_edit_keys(const void* K_in, void* K_out, const seka_shape* sh, 
   seka_status rc = check_shape(sh, false);
   if (rc != SEKA_OK) return rc;
   if (!K_in || !K_out || !st) return SEKA_ERR_NULL;
+  if (sh->B > kMaxGridYZ) return SEKA_ERR_SHAPE;
   rc = check_steer(st, sh);
   if (rc != SEKA_OK) return rc;
   if (misaligned(K_in) || misaligned(K_out)) return SEKA_ERR_ALIGN;
@@ -247,6 +245,7 @@ seka_status seka_edit_keys_packed(const void* K_in, void* K_out, const seka_shap
   seka_status rc = check_shape(sh, false);
   if (rc != SEKA_OK) return rc;
   if (!K_in || !K_out || !st || !cu_seqlens) return SEKA_ERR_NULL;
+  if (sh->B > kMaxGridYZ) return SEKA_ERR_SHAPE;
   rc = check_steer(st, sh);
   if (rc != SEKA_OK) return rc;
   if (total_tokens < 1 || total_tokens > 0x7fffffffLL) return SEKA_ERR_SHAPE;
@@ -266,12 +265,14 @@ size_t seka_decode_workspace_bytes(const seka_shape* sh) {
   return seka::decode_workspace_bytes(sh->B, sh->S, sh->Hq, sh->Hkv, sh->D);
 }
 
-seka_status seka_attention_decode(const void* q, const void* K, const void* V, void* O, float* lse,
-                                  const int32_t* seq_lens, const seka_shape* sh, void* workspace,
-                                  size_t workspace_bytes, void* hip_stream) {
+namespace {
+// Validation shared by the two generation-step entry points; *need = bytes of partial states the launch writes.
+seka_status check_decode(const void* q, const void* K, const void* V, void* O, float* lse, const int32_t* seq_lens,
+                         const seka_shape* sh, size_t* need) {
   seka_status rc = check_shape(sh, true);
   if (rc != SEKA_OK) return rc;
   if (!q || !K || !V || !O) return SEKA_ERR_NULL;
+  if (sh->B > kMaxGridYZ) return SEKA_ERR_SHAPE;
   if (misaligned(q) || misaligned(K) || misaligned(V) || misaligned(O)) return SEKA_ERR_ALIGN;
   if ((lse && (reinterpret_cast<uintptr_t>(lse) & 3u)) || (seq_lens && (reinterpret_cast<uintptr_t>(seq_lens) & 3u)))
     return SEKA_ERR_ALIGN;
@@ -279,7 +280,17 @@ seka_status seka_attention_decode(const void* q, const void* K, const void* V, v
   const size_t nq = (size_t)sh->B * sh->Hq * sh->D * es;
   const size_t nk = (size_t)sh->B * sh->S * sh->Hkv * sh->D * es;
   if (ranges_overlap(O, nq, q, nq) || ranges_overlap(O, nq, K, nk) || ranges_overlap(O, nq, V, nk)) return SEKA_ERR_ALIAS;
-  const size_t need = seka::decode_workspace_bytes(sh->B, sh->S, sh->Hq, sh->Hkv, sh->D);
+  *need = seka::decode_workspace_bytes(sh->B, sh->S, sh->Hq, sh->Hkv, sh->D);
+  return SEKA_OK;
+}
+}  // namespace
+
+seka_status seka_attention_decode(const void* q, const void* K, const void* V, void* O, float* lse,
+                                  const int32_t* seq_lens, const seka_shape* sh, void* workspace,
+                                  size_t workspace_bytes, void* hip_stream) {
+  size_t need = 0;
+  seka_status rc = check_decode(q, K, V, O, lse, seq_lens, sh, &need);
+  if (rc != SEKA_OK) return rc;
   if (!workspace || workspace_bytes < need) return SEKA_ERR_WORKSPACE;
   if (misaligned(workspace)) return SEKA_ERR_ALIGN;
   const float scale = sh->softmax_scale > 0.0f ? sh->softmax_scale : 1.0f / std::sqrt((float)sh->D);

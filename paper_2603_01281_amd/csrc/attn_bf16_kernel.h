@@ -13,12 +13,6 @@
 //   O^T = V^T P^T : B = P^T taken straight from the S^T accumulators (the contraction order over
 //                   keys is permuted identically on the V side), A = V^T fragments fetched from the
 //                   row-major V tile with the transposing LDS read (ds_read_b64_tr_b16).
-// Ping-pong (MODE 1): a SIMD hosts two waves of the workgroup.  Both would otherwise run the same
-//   phase at the same time (matrix pipe idle while both exponentiate, vector ALU idle while both
-//   multiply).  The waves of the second half of the workgroup therefore run one phase ahead: they
-//   enter an iteration with S^T of the current tile already computed and order their work
-//   softmax -> PV -> next S^T, while the first half orders it S^T -> softmax -> PV.  K tiles live
-//   in three LDS buffers so that both the current and the next tile are readable.
 // Key edit (STEER): after a K tile lands in LDS, a wave ballot of its mask bytes tells whether it
 //   holds highlighted tokens; if so, 16-key blocks with highlights get
 //   Z^T = U_cat^T K^T and K'^T = K^T + U_cat (c .* Z^T) on 16x16x32 MFMAs, written back to LDS as bf16.
@@ -30,10 +24,9 @@ namespace seka {
 constexpr int ATT_BK = 64;   // keys per tile
 
 __host__ __device__ constexpr int att_kld(int D) { return D + 8; }     // K tile row stride (elements)
-__host__ __device__ constexpr int att_nkb(int mode) { return mode >= 1 ? 3 : 2; }
 
-inline size_t attention_bf16_smem_bytes(int D, int vpad, int mode, bool steer, int Rpad) {
-  size_t n = ((size_t)att_nkb(mode) * ATT_BK * att_kld(D) + 2 * (size_t)ATT_BK * (D + vpad)) * 2;
+inline size_t attention_bf16_smem_bytes(int D, int vpad, bool steer, int Rpad) {
+  size_t n = ((size_t)2 * ATT_BK * att_kld(D) + 2 * (size_t)ATT_BK * (D + vpad)) * 2;
   if (steer) n += (size_t)D * (Rpad + 8) * 2 + (size_t)Rpad * 4;
   return n;
 }
@@ -48,7 +41,7 @@ __device__ __forceinline__ bf16x8 lds_read_tr_pair(const uint16_t* p0, const uin
   return __builtin_shufflevector(lo4, hi4, 0, 1, 2, 3, 4, 5, 6, 7);
 }
 
-template <int D, int HPW, int RB, bool STEER, int VPAD, int MODE, int ABL = 0>
+template <int D, int HPW, int RB, bool STEER, int VPAD>
 __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs a, SteerArgs st, int Rpad) {
   constexpr int NW = HPW * RB;
   constexpr int NT = 64 * NW;
@@ -58,7 +51,7 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
   constexpr int VLD = D + VPAD;
   constexpr int K_ELEMS = BK * KLD;
   constexpr int V_ELEMS = BK * VLD;
-  constexpr int NKB = att_nkb(MODE);  // K buffers in LDS
+  constexpr int NKB = 2;              // K buffers in LDS
   constexpr int KS = D / 16;          // contraction steps of S^T = K Q^T
   constexpr int DB = D / 32;          // 32-row blocks of O^T
   constexpr int CPR = D / 8;          // 16-byte chunks per tile row
@@ -263,13 +256,8 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
     for (int ks = 0; ks < KS; ++ks) {
       const bf16x8 a0 = *reinterpret_cast<const bf16x8*>(Kb + l32 * KLD + 16 * ks + 8 * hf);
       const bf16x8 a1 = *reinterpret_cast<const bf16x8*>(Kb + (32 + l32) * KLD + 16 * ks + 8 * hf);
-      if (ABL == 4) {          // timing experiment: QK product replaced by one VALU op per fragment
-        s0[ks] += (float)a0[0];
-        s1[ks] += (float)a1[0];
-      } else {
-        s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[ks], s0, 0, 0, 0);
-        s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[ks], s1, 0, 0, 0);
-      }
+      s0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[ks], s0, 0, 0, 0);
+      s1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a1, qf[ks], s1, 0, 0, 0);
     }
   };
   // causal mask of tile t, only where the tile reaches past the wave's first row
@@ -286,17 +274,6 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
   };
   // online softmax of one tile: scores -> packed P^T, running max / sum, rescale of O when a max moved
   auto softmax_tile = [&](f32x16& s0, f32x16& s1, bf16x8 (&pb)[4]) {
-    if (ABL == 2) {            // timing experiment: no softmax at all, only the bf16 packing
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        pb[0][e] = (__bf16)s0[e];
-        pb[1][e] = (__bf16)s0[8 + e];
-        pb[2][e] = (__bf16)s1[e];
-        pb[3][e] = (__bf16)s1[8 + e];
-      }
-      l_run += 1.f;
-      return;
-    }
     float mx = fmaxf(s0[0], s1[0]);
 #pragma unroll
     for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s0[r], s1[r]));
@@ -307,13 +284,8 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
     float lsum = 0.f;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      if (ABL == 1) {          // timing experiment: no exponentials
-        s0[r] = s0[r] * c2 - mc;
-        s1[r] = s1[r] * c2 - mc;
-      } else {
-        s0[r] = __builtin_amdgcn_exp2f(s0[r] * c2 - mc);
-        s1[r] = __builtin_amdgcn_exp2f(s1[r] * c2 - mc);
-      }
+      s0[r] = __builtin_amdgcn_exp2f(s0[r] * c2 - mc);
+      s1[r] = __builtin_amdgcn_exp2f(s1[r] * c2 - mc);
       lsum += s0[r] + s1[r];
     }
     l_run = l_run * alpha + lsum;
@@ -342,11 +314,7 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
       for (int db = 0; db < DB; ++db) {
         const uint16_t* p = vbase + (16 * kb) * VLD + 32 * db;
         const bf16x8 va = lds_read_tr_pair(p, p + 8 * VLD);
-        if (ABL == 3) {        // timing experiment: PV product replaced by one VALU op per fragment
-          oacc[db][kb] += (float)va[0] + (float)pb[kb][0];
-        } else {
-          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[kb], oacc[db], 0, 0, 0);
-        }
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[kb], oacc[db], 0, 0, 0);
       }
     }
   };
@@ -355,108 +323,43 @@ __global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs 
   const int tw_last = wave_rows_exist ? min(ntiles - 1, (qw + 31) / BK) : -1;   // last tile this wave computes on
   unsigned long long hl = 0ull;
 
-  if (MODE == 0) {
-    // ---------------- simple loop: load(t+1) | S(t), softmax(t), PV(t) | store(t+1) ----------------
-    load_rows(Kg, 0, kpre);
-    load_rows(Vg, 0, vpre);
-    load_mask(0);
-    store_rows(Kt, KLD, kpre);
-    store_rows(Vt, VLD, vpre);
-    hl = tile_ballot();
+  // ---------------- simple loop: load(t+1) | S(t), softmax(t), PV(t) | store(t+1) ----------------
+  load_rows(Kg, 0, kpre);
+  load_rows(Vg, 0, vpre);
+  load_mask(0);
+  store_rows(Kt, KLD, kpre);
+  store_rows(Vt, VLD, vpre);
+  hl = tile_ballot();
+  __syncthreads();
+  if (STEER && hl != 0ull) {
+    edit_tile(Kt, hl);
     __syncthreads();
-    if (STEER && hl != 0ull) {
-      edit_tile(Kt, hl);
-      __syncthreads();
+  }
+  for (int t = 0; t < ntiles; ++t) {
+    const int buf = t & 1;
+    const bool more = t + 1 < ntiles;
+    if (more) {
+      load_rows(Kg, t + 1, kpre);
+      load_rows(Vg, t + 1, vpre);
+      load_mask(t + 1);
     }
-    for (int t = 0; t < ntiles; ++t) {
-      const int buf = t & 1;
-      const bool more = t + 1 < ntiles;
-      if (more) {
-        load_rows(Kg, t + 1, kpre);
-        load_rows(Vg, t + 1, vpre);
-        load_mask(t + 1);
-      }
-      if (t <= tw_last) {
-        f32x16 s0, s1;
-        bf16x8 pb[4];
-        qk_tile(Kt + buf * K_ELEMS, s0, s1);
-        causal_mask(t, s0, s1);
-        softmax_tile(s0, s1, pb);
-        pv_tile(Vt + buf * V_ELEMS, pb);
-      }
-      if (more) {
-        store_rows(Kt + (buf ^ 1) * K_ELEMS, KLD, kpre);
-        store_rows(Vt + (buf ^ 1) * V_ELEMS, VLD, vpre);
-        hl = tile_ballot();
-      }
-      __syncthreads();
-      if (STEER && more && hl != 0ull) {
-        edit_tile(Kt + (buf ^ 1) * K_ELEMS, hl);
-        __syncthreads();
-      }
+    if (t <= tw_last) {
+      f32x16 s0, s1;
+      bf16x8 pb[4];
+      qk_tile(Kt + buf * K_ELEMS, s0, s1);
+      causal_mask(t, s0, s1);
+      softmax_tile(s0, s1, pb);
+      pv_tile(Vt + buf * V_ELEMS, pb);
     }
-  } else {
-    // ---------------- ping-pong: during iteration t LDS holds K(t) in Kbuf[t%3], K(t+1) in Kbuf[(t+1)%3],
-    // V(t) in Vbuf[t&1]; K(t+2) and V(t+1) travel through registers and are stored at the end of iteration t.
-    load_rows(Kg, 0, kpre);
-    load_rows(Vg, 0, vpre);
-    load_mask(0);
-    store_rows(Kt, KLD, kpre);
-    store_rows(Vt, VLD, vpre);
-    hl = tile_ballot();
-    unsigned long long hl1 = 0ull;
-    if (ntiles > 1) {
-      load_rows(Kg, 1, kpre);
-      load_mask(1);
-      store_rows(Kt + K_ELEMS, KLD, kpre);
-      hl1 = tile_ballot();
+    if (more) {
+      store_rows(Kt + (buf ^ 1) * K_ELEMS, KLD, kpre);
+      store_rows(Vt + (buf ^ 1) * V_ELEMS, VLD, vpre);
+      hl = tile_ballot();
     }
     __syncthreads();
-    if (STEER && (hl | hl1) != 0ull) {
-      if (hl != 0ull) edit_tile(Kt, hl);
-      if (hl1 != 0ull) edit_tile(Kt + K_ELEMS, hl1);
+    if (STEER && more && hl != 0ull) {
+      edit_tile(Kt + (buf ^ 1) * K_ELEMS, hl);
       __syncthreads();
-    }
-    const bool ahead = MODE == 1 ? wave >= (NW + 1) / 2 : (wave & 1) != 0;   // which waves run one phase ahead
-    f32x16 s0, s1;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) { s0[r] = 0.f; s1[r] = 0.f; }
-    if (ahead && 0 <= tw_last) qk_tile(Kt, s0, s1);
-    int kb_cur = 0;                                // t % 3
-    for (int t = 0; t < ntiles; ++t) {
-      const bool moreK = t + 2 < ntiles, moreV = t + 1 < ntiles;
-      const int kb_next = kb_cur == 2 ? 0 : kb_cur + 1;
-      const int kb_free = kb_next == 2 ? 0 : kb_next + 1;
-      if (moreK) {
-        load_rows(Kg, t + 2, kpre);
-        load_mask(t + 2);
-      }
-      if (moreV) load_rows(Vg, t + 1, vpre);
-      if (t <= tw_last) {
-        bf16x8 pb[4];
-        if (!ahead) {
-          qk_tile(Kt + kb_cur * K_ELEMS, s0, s1);
-          causal_mask(t, s0, s1);
-          softmax_tile(s0, s1, pb);
-          pv_tile(Vt + (t & 1) * V_ELEMS, pb);
-        } else {
-          causal_mask(t, s0, s1);
-          softmax_tile(s0, s1, pb);
-          pv_tile(Vt + (t & 1) * V_ELEMS, pb);
-          if (t + 1 <= tw_last) qk_tile(Kt + kb_next * K_ELEMS, s0, s1);
-        }
-      }
-      if (moreK) {
-        store_rows(Kt + kb_free * K_ELEMS, KLD, kpre);
-        hl = tile_ballot();
-      }
-      if (moreV) store_rows(Vt + ((t + 1) & 1) * V_ELEMS, VLD, vpre);
-      __syncthreads();
-      if (STEER && moreK && hl != 0ull) {
-        edit_tile(Kt + kb_free * K_ELEMS, hl);
-        __syncthreads();
-      }
-      kb_cur = kb_next;
     }
   }
 

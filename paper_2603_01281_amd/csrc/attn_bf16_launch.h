@@ -1,20 +1,19 @@
-// Launch-side dispatch of the bf16 attention kernel for one head dimension (instantiated per D in its own
-// translation unit so the variants compile in parallel).
+// Launch-side dispatch of the bf16 attention kernels for one head dimension (instantiated per D in its own
+// translation unit so that the instantiations compile in parallel).
 #pragma once
 #include <cstring>
 #include "attn_bf16_kernel.h"
 
 namespace seka {
 
-// variant id -> (V tile row padding in elements, loop structure); 0 is the library default
-constexpr int kNumAttnVariants = 8;
+constexpr int kAttnVPad = 32;    // row padding of the register-staged kernel's V tile (elements)
 
-template <int D, int HPW, int RB, bool STEER, int VPAD, int MODE, int ABL = 0>
+template <int D, int HPW, int RB, bool STEER>
 hipError_t launch_attention_bf16_cfg(const AttnArgs& a, const SteerArgs* steer, hipStream_t s) {
   constexpr int BQ = 32 * RB;
   const int Rpad = STEER ? (steer->M * steer->r + 31) / 32 * 32 : 0;
-  const size_t smem = attention_bf16_smem_bytes(D, VPAD, MODE, STEER, Rpad);
-  auto kernel = attention_bf16_kernel<D, HPW, RB, STEER, VPAD, MODE, ABL>;
+  const size_t smem = attention_bf16_smem_bytes(D, kAttnVPad, STEER, Rpad);
+  auto kernel = attention_bf16_kernel<D, HPW, RB, STEER, kAttnVPad>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
   if (e != hipSuccess) return e;
@@ -41,43 +40,30 @@ inline hipError_t launch_attention_bf16_pipe(const AttnArgs& a, const SteerArgs*
   return launch_attention_bf16_pipe_r128(a, steer, s);
 }
 
-template <int D, bool STEER, int VPAD, int MODE>
+template <int D, bool STEER>
 hipError_t launch_attention_bf16_group(const AttnArgs& a, const SteerArgs* steer, hipStream_t s) {
   const int G = a.Hq / a.Hkv;
-  if (G % 4 == 0) return launch_attention_bf16_cfg<D, 4, 2, STEER, VPAD, MODE>(a, steer, s);
-  if (G % 7 == 0) return launch_attention_bf16_cfg<D, 7, 1, STEER, VPAD, MODE>(a, steer, s);
-  if (G % 2 == 0) return launch_attention_bf16_cfg<D, 2, 4, STEER, VPAD, MODE>(a, steer, s);
-  return launch_attention_bf16_cfg<D, 1, 8, STEER, VPAD, MODE>(a, steer, s);
+  if (G % 4 == 0) return launch_attention_bf16_cfg<D, 4, 2, STEER>(a, steer, s);
+  if (G % 7 == 0) return launch_attention_bf16_cfg<D, 7, 1, STEER>(a, steer, s);
+  if (G % 2 == 0) return launch_attention_bf16_cfg<D, 2, 4, STEER>(a, steer, s);
+  return launch_attention_bf16_cfg<D, 1, 8, STEER>(a, steer, s);
 }
 
 template <int D, bool STEER>
-hipError_t launch_attention_bf16_variant(const AttnArgs& a, const SteerArgs* steer, int variant, hipStream_t s) {
-  switch (variant) {
-    case 0:
-      if (D == 128) {
-        const hipError_t e = launch_attention_bf16_pipe(a, steer, s);
-        if (e != hipErrorNotSupported) return e;     // highlight bitmap too large for LDS at this S: register-staged kernel
-      }
-      return launch_attention_bf16_group<D, STEER, 32, 0>(a, steer, s);
-#ifdef SEKA_TUNING_VARIANTS
-    case 1: return launch_attention_bf16_group<D, STEER, 32, 0>(a, steer, s);
-    case 2: return launch_attention_bf16_group<D, STEER, 32, 1>(a, steer, s);
-    case 4: return launch_attention_bf16_cfg<D, 4, 2, STEER, 32, 0, 1>(a, steer, s);   // timing experiments (wrong results)
-    case 5: return launch_attention_bf16_cfg<D, 4, 2, STEER, 32, 0, 2>(a, steer, s);
-    case 6: return launch_attention_bf16_cfg<D, 4, 2, STEER, 32, 0, 3>(a, steer, s);
-    case 7: return launch_attention_bf16_cfg<D, 4, 2, STEER, 32, 0, 4>(a, steer, s);
-#endif
-    default: return hipErrorNotSupported;
+hipError_t launch_attention_bf16_any(const AttnArgs& a, const SteerArgs* steer, hipStream_t s) {
+  if (D == 128) {
+    const hipError_t e = launch_attention_bf16_pipe(a, steer, s);
+    if (e != hipErrorNotSupported) return e;     // highlight bitmap too large for LDS at this S: register-staged kernel
   }
+  return launch_attention_bf16_group<D, STEER>(a, steer, s);
 }
 
 template <int D>
-hipError_t launch_attention_bf16_d(const AttnArgs& a, const SteerArgs* steer, int variant, hipStream_t s) {
-  return steer ? launch_attention_bf16_variant<D, true>(a, steer, variant, s)
-               : launch_attention_bf16_variant<D, false>(a, steer, variant, s);
+hipError_t launch_attention_bf16_d(const AttnArgs& a, const SteerArgs* steer, hipStream_t s) {
+  return steer ? launch_attention_bf16_any<D, true>(a, steer, s) : launch_attention_bf16_any<D, false>(a, steer, s);
 }
 
-hipError_t launch_attention_bf16_d128(const AttnArgs& a, const SteerArgs* steer, int variant, hipStream_t s);
-hipError_t launch_attention_bf16_d64(const AttnArgs& a, const SteerArgs* steer, int variant, hipStream_t s);
+hipError_t launch_attention_bf16_d128(const AttnArgs& a, const SteerArgs* steer, hipStream_t s);
+hipError_t launch_attention_bf16_d64(const AttnArgs& a, const SteerArgs* steer, hipStream_t s);
 
 }  // namespace seka

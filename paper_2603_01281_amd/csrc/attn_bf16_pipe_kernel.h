@@ -89,11 +89,6 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   constexpr int SPW = (SLOTS + NW - 1) / NW;             // load instructions per wave per tensor per tile
   constexpr int TB = DMA_TILE_BYTES;
 
-#ifdef SEKA_CYCLE_PROBE
-  // Diagnostic build: per-wave shader-clock counters, written over the LSE rows of the wave's first queries.
-  unsigned long long prb_entry = __builtin_amdgcn_s_memtime();
-  unsigned long long prb_edit = 0ull, prb_n = 0ull, prb_wait = 0ull, prb_bar = 0ull, prb_issued = 0ull;
-#endif
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   unsigned char* Kst = smem;                                     // [3][16 KB] swizzled K tiles
   unsigned char* Vst = smem + DMA_STAGES * TB;                   // [3][16 KB] swizzled V tiles
@@ -632,9 +627,6 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   const bool wave_rows_exist = qw < S;
   const int tw_last = wave_rows_exist ? min(ntiles - 1, (qw + WR - 1) / BK) : -1;   // last tile this wave computes on
 
-#ifdef SEKA_CYCLE_PROBE
-  if (pass == 0) prb_issued = __builtin_amdgcn_s_memtime();
-#endif
   // ---- prologue: wait for the first tiles, edit K(0) and K(1), first block of S^T ----
   dma_wait_vmcnt<0>();   // also covers the Q, U and mask loads issued after the tile loads
 #pragma unroll
@@ -642,10 +634,6 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qf[rp][ks]));   // pin the compiler's own wait for Q here, not in the loop
   dma_barrier();
-#ifdef SEKA_CYCLE_PROBE
-  const unsigned long long prb_start = __builtin_amdgcn_s_memtime();
-  const unsigned long long prb_rstart = __builtin_amdgcn_s_memrealtime();
-#endif
   unsigned long long anyw = 0ull;      // bit i: tile 64 (t / 64) + i holds a highlighted key (0 when not steering)
   // Next tile index at which the loop has something to do besides attention: a tile with highlighted keys, or
   // the start of the next group of 64 tiles (summary reload).  Scalar; the loop compares one integer per tile.
@@ -701,20 +689,9 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     }
   };
   auto bottom = [&](auto sure_c, int t) __attribute__((always_inline)) {
-#ifdef SEKA_CYCLE_PROBE
-    const unsigned long long w0 = __builtin_amdgcn_s_memtime();
-#endif
     if (decltype(sure_c)::value || t + 1 < ntiles) dma_wait_vmcnt<SPW>();   // all but the V loads of this iteration
     else dma_wait_vmcnt<0>();
-#ifdef SEKA_CYCLE_PROBE
-    const unsigned long long w1 = __builtin_amdgcn_s_memtime();
     dma_barrier();
-    const unsigned long long w2 = __builtin_amdgcn_s_memtime();
-    prb_wait += w1 - w0;
-    prb_bar += w2 - w1;
-#else
-    dma_barrier();
-#endif
   };
 
   // Steering events of the tile that landed at the bottom of the previous iteration (tile t + 1 in iteration t):
@@ -731,17 +708,10 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
       if (sh == 0u) anyw = any_word(tn);
       tile_evt = next_event(tn);
       if ((anyw >> sh) & 1ull) {
-#ifdef SEKA_CYCLE_PROBE
-        const unsigned long long c0 = __builtin_amdgcn_s_memtime();
-#endif
         edit_tile(Kst + (tn % 3) * TB, hlbits[tn]);
         dma_barrier();
 #pragma unroll
         for (int i = 0; i < 2; ++i) kp[i] = *(pipe_lds_bf16x8_ptr)(uintptr_t)(kaddr[i] + knext_off);
-#ifdef SEKA_CYCLE_PROBE
-        prb_edit += __builtin_amdgcn_s_memtime() - c0;
-        prb_n += 1;
-#endif
       }
     }
   };
@@ -879,9 +849,6 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     bottom(std::false_type{}, t);
     ++t;
   }
-#ifdef SEKA_CYCLE_PROBE
-  const unsigned long long prb_tail = __builtin_amdgcn_s_memtime();
-#endif
   // ---- up to two more full tiles before the wave's last one: same pipelined step, ring stage known at run time ----
 #pragma nounroll
   for (; t < tw_last; ++t) {
@@ -935,22 +902,6 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   }
   if (owed) pv_half(owed_off, pb);
 
-#ifdef SEKA_CYCLE_PROBE
-  if (a.lse && lane == 0 && qi0 < S) {
-    float* dp = a.lse + lse_index(a, b, hq, tok0, qi0);
-    dp[0] = (float)(prb_start - prb_entry);                          // set-up until the first tiles are usable
-    dp[1] = (float)(__builtin_amdgcn_s_memtime() - prb_start);       // loops of this block
-    dp[2] = (float)(__builtin_amdgcn_s_memrealtime() - prb_rstart);  // the same span in 100 MHz ticks
-    dp[3] = (float)prb_wait;                                         // waiting for tile loads
-    dp[4] = (float)prb_bar;                                          // waiting at the per-tile barrier
-    dp[5] = (float)prb_edit;                                         // key edits incl. their barrier
-    dp[6] = (float)prb_n;
-    dp[7] = (float)(prb_tail - prb_start);                           // prologue edits and pipelined iterations
-    dp[8] = (float)(prb_issued - prb_entry);                         // set-up until every load has been issued
-  }
-  prb_edit = prb_n = prb_wait = prb_bar = 0ull;
-  prb_entry = __builtin_amdgcn_s_memtime();
-#endif
   // ---- next block's first loads (after a barrier: the last PV product above still read the V ring), then this
   // block's output ----
   const int qi_out = qi0;
@@ -964,9 +915,6 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     ntiles = last_key / BK + 1;
     begin_block();
   }
-#ifdef SEKA_CYCLE_PROBE
-  prb_issued = __builtin_amdgcn_s_memtime();
-#endif
 #pragma unroll
   for (int rp = 0; rp < RPW; ++rp) {
     const int qi = qi_out + 32 * rp;
@@ -984,10 +932,8 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
           *reinterpret_cast<uint2*>(op + 32 * db + 8 * q4) = __builtin_bit_cast(uint2, o4);
         }
       }
-#ifndef SEKA_CYCLE_PROBE
       // m_run is the reference exponent in units of s * scale * log2(e); l_tot is relative to it
       if (a.lse && hf == 0) a.lse[lse_index(a, b, hq, tok0, qi)] = m_run[rp] * 0.6931471805599453f + logf(l_tot);
-#endif
     }
   }
   if (!more) break;

@@ -41,8 +41,7 @@ struct AttnArgs {
 
 // Launchers (defined one per .hip file).  `steer` may be nullptr for plain attention.
 hipError_t launch_attention_f32(const AttnArgs& a, const SteerArgs* steer, hipStream_t s);
-hipError_t launch_attention_bf16(const AttnArgs& a, const SteerArgs* steer, int variant, hipStream_t s);
-bool attention_bf16_variant_ok(int variant);
+hipError_t launch_attention_bf16(const AttnArgs& a, const SteerArgs* steer, hipStream_t s);
 hipError_t launch_edit_keys(const void* K_in, void* K_out, int B, int S, int Hkv, int D, int dtype,
                             const SteerArgs& steer, hipStream_t s, const int* cu = nullptr, int total = 0);
 size_t route_workspace_bytes(int B, int Hkv, int D, int t0, int t1);

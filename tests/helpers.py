@@ -51,18 +51,30 @@ def oracle_inputs(inp):
 def assert_close_bf16(got, ref, what=""):
     d = np.abs(got - ref)
     assert np.isfinite(got).all(), f"{what}: non-finite output"
+    print(f"[O bf16] {what}: max {d.max():.3g} mean {d.mean():.3g}", flush=True)
     assert d.max() <= BF16_MAX, f"{what}: max |diff| {d.max():.4g} > {BF16_MAX}"
     assert d.mean() <= BF16_MEAN, f"{what}: mean |diff| {d.mean():.4g} > {BF16_MEAN}"
 
 
-def assert_lse_close_bf16(got, ref, what=""):
-    """LSE moves by at most the largest score error of the row.  Keys edited on chip are rounded to bf16
-    before scoring, so a score carries an error of about 2^-9 |q||k'| / sqrt(D) ~ 2e-3 rms (worst rows
-    ~1e-2) for unit-variance inputs; a row with a single dominant key inherits it undamped.
-    Hence the same 2e-2 bound as for O, with no bound on the mean."""
+# LSE = m + log(l) per query row, bf16 paths.  Error sources, per path:
+#   plain / decode: scores are exact products accumulated in fp32 (~1e-6); the row sum l is formed from the
+#     probabilities AFTER their rounding to bf16 (the values the PV product uses), each off by at most 2^-8
+#     relative (round to nearest, 8 significant bits), so l and hence log(l) are off by at most 2^-8 = 3.9e-3,
+#     reached only by a row that one key dominates; over many keys the roundings average out.
+#   steered, edit on chip: on top of that, an edited key is rounded to bf16 before scoring (and its subspace
+#     coordinates before the second product), so its score carries about 2^-8 |q||k'| scale / sqrt(3 D) ~ 2e-3 rms
+#     (worst keys ~1e-2 for unit-variance inputs); LSE moves by the probability-weighted mean of these errors,
+#     which a row with one dominant highlighted key inherits undamped.
+LSE_BOUNDS = {"steered": (2e-2, 2e-3), "plain": (5e-3, 5e-4), "decode": (5e-3, 5e-4)}
+
+
+def assert_lse_close_bf16(got, ref, what="", path="steered"):
+    mx, mean = LSE_BOUNDS[path]
     d = np.abs(got - ref)
     assert np.isfinite(got).all(), f"{what}: non-finite output"
-    assert d.max() <= BF16_MAX, f"{what}: max |diff| {d.max():.4g} > {BF16_MAX}"
+    print(f"[lse {path}] {what}: max {d.max():.3g} mean {d.mean():.3g}", flush=True)
+    assert d.max() <= mx, f"{what}: max |diff| {d.max():.4g} > {mx}"
+    assert d.mean() <= mean, f"{what}: mean |diff| {d.mean():.4g} > {mean}"
 
 
 def assert_close_f32(got, ref, what="", tol=F32_ABS):

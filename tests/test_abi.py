@@ -20,7 +20,7 @@ def test_exports_every_declared_symbol(B):
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     names = set(re.findall(r"\b(seka_[a-z_0-9]+)\s*\(", header))
     assert {"seka_route", "seka_edit_keys", "seka_attention_prefill", "seka_attention_plain",
-            "seka_route_workspace_bytes", "seka_status_string", "seka_set_tuning",
+            "seka_route_workspace_bytes", "seka_status_string",
             "seka_attention_decode", "seka_decode_workspace_bytes", "seka_attention_prefill_ragged",
             "seka_learn_workspace_bytes", "seka_learn_projection", "seka_head_distance",
             "seka_attention_prefill_packed", "seka_route_ragged", "seka_route_ragged_workspace_bytes", "seka_edit_keys_packed", "seka_project_route",
@@ -159,12 +159,6 @@ def test_project_route_rejects_bad_arguments(B):
     assert call(mode=9) == 6
 
 
-def test_tuning_rejects_unknown(B):
-    assert B.lib.seka_set_tuning(99, 0) == 6
-    assert B.lib.seka_set_tuning(0, 12345) == 6
-    assert B.lib.seka_set_tuning(0, 0) == 0
-
-
 def test_decode_rejects_bad_arguments(B):
     L = B.lib
     ok = _shape(B)
@@ -230,3 +224,17 @@ def test_packed_rejects_bad_arguments(B):
     assert call(total=1 << 31) == 2
     assert call(sh=_shape(B, Hq=5)) == 2
     assert call(o=q) == 5
+
+
+def test_batch_sizes_beyond_a_grid_axis_are_rejected(B):
+    """The routing, edit and decode launches carry the batch on a grid axis limited to 65535 workgroups: larger
+    batches are a shape error on the host, not a failed launch."""
+    L = B.lib
+    big = B.seka_shape(70000, 16, 4, 1, 64, B.SEKA_F32, 0.0)
+    assert L.seka_route(FAKE, ctypes.byref(big), FAKE * 2, 2, 0, 16, 0, 10.0, FAKE * 3, FAKE * 4, 1 << 40, None) == 2
+    assert L.seka_route(FAKE, ctypes.byref(B.seka_shape(40000, 16, 4, 2, 64, B.SEKA_F32, 0.0)), FAKE * 2, 2, 0, 16, 0, 10.0,
+                        FAKE * 3, FAKE * 4, 1 << 40, None) == 2          # B * Hkv counts
+    st = _steer(B, Hkv=1)
+    assert L.seka_edit_keys(FAKE, FAKE * 1000, ctypes.byref(big), ctypes.byref(st), None) == 2
+    assert L.seka_attention_decode(FAKE, FAKE * 4, FAKE * 8, FAKE * 64, None, None, ctypes.byref(big), FAKE * 128,
+                                   1 << 40, None) == 2

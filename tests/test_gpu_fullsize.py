@@ -1,8 +1,10 @@
 """GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
-The full score matrix is too large for the host there, so the oracle computes a seeded sample of
-output rows one by one (rows are independent given the edited keys), always including the first and
-last row, rows around tile boundaries and rows around every highlighted span.  Edited keys and routing
-weights are compared in full."""
+Configuration 2 and one whole batch entry of configuration 3's first steered layer are compared in full
+(every row of every head).  Beyond that the full score matrix is too large for the host, so the oracle
+computes a seeded sample of output rows one by one (rows are independent given the edited keys), always
+including the first and last row, rows around tile boundaries and rows around every highlighted span.
+Edited keys and routing weights are compared in full, and two launches on the same inputs must agree bit
+for bit at the largest shapes (no atomics, fixed reduction orders)."""
 import numpy as np
 import pytest
 
@@ -37,17 +39,51 @@ def _check_rows(seka, inp, dev, rows, w_dev=None, w_ref=None, steered=True, what
     got_o = O[idx[:, 0], idx[:, 2], idx[:, 1]].float().cpu().numpy().astype(np.float64)
     got_l = lse[idx[:, 0], idx[:, 1], idx[:, 2]].cpu().numpy().astype(np.float64)
     H.assert_close_bf16(got_o, ref_o, f"{what} O rows")
-    H.assert_lse_close_bf16(got_l, ref_l, f"{what} LSE rows")
+    H.assert_lse_close_bf16(got_l, ref_l, f"{what} LSE rows", path="steered" if steered else "plain")
     return O
 
 
+def _full_compare(seka, inp, dev, o, steered, what):
+    """Every row of every head of `inp` against the oracle's full score matrix."""
+    import torch
+    O = torch.full_like(dev.Q, float("nan"))
+    lse = dev.lse_buffer()
+    if steered:
+        seka.seka_attention_prefill(dev.Q, dev.K, dev.V, O, dev.U, dev.gain, dev.mask, lse=lse, scale=inp.scale)
+        ref_O, ref_L = orc.steered_attention(o["Q"], o["K"], o["V"], o["U"], inp.gain, inp.mask, scale=inp.scale)
+    else:
+        seka.seka_attention_plain(dev.Q, dev.K, dev.V, O, lse=lse, scale=inp.scale)
+        ref_O, ref_L = orc.causal_attention(o["Q"], o["K"], o["V"], scale=inp.scale)
+    torch.cuda.synchronize()
+    H.assert_close_bf16(H.to_f64(O), ref_O, f"{what} O (all rows)")
+    H.assert_lse_close_bf16(H.to_f64(lse), ref_L, f"{what} LSE (all rows)", path="steered" if steered else "plain")
+    return O
+
+
+def _two_runs_identical(seka, dev, inp, steered, what, w=None):
+    import torch
+    outs = []
+    for _ in range(2):
+        O = torch.full_like(dev.Q, float("nan"))
+        lse = dev.lse_buffer()
+        if steered:
+            seka.seka_attention_prefill(dev.Q, dev.K, dev.V, O, dev.U, dev.gain, dev.mask, w=w, lse=lse, scale=inp.scale)
+        else:
+            seka.seka_attention_plain(dev.Q, dev.K, dev.V, O, lse=lse, scale=inp.scale)
+        torch.cuda.synchronize()
+        outs.append((O, lse))
+    assert torch.equal(outs[0][0], outs[1][0]), f"{what}: two launches differ in O"
+    assert torch.equal(outs[0][1], outs[1][1]), f"{what}: two launches differ in LSE"
+
+
 def test_cfg2_full_size(seka):
+    """Configuration 2 compared in full: all 4096 rows of all 32 heads, steered and plain."""
     inp = inputs.make_config(2, seed=0)
-    _say("cfg2 full size")
+    _say("cfg2 full size, all rows")
     dev = H.DeviceInputs(inp)
-    rows = H.sample_rows(inp, per_head=24, seed=1)
-    O_s = _check_rows(seka, inp, dev, rows, steered=True, what="cfg2 steered")
-    O_p = _check_rows(seka, inp, dev, rows, steered=False, what="cfg2 plain")
+    o = H.oracle_inputs(inp)
+    O_s = _full_compare(seka, inp, dev, o, True, "cfg2 steered")
+    O_p = _full_compare(seka, inp, dev, o, False, "cfg2 plain")
     # property that holds at any size: rows before the first highlighted token cannot see an edited key
     first = min(s for s, _ in inp.spans[0])
     import torch
@@ -56,16 +92,29 @@ def test_cfg2_full_size(seka):
 
 
 def test_cfg3_layer_full_size(seka):
-    """One steered layer of the 32-layer stack (layer 8, the first steered one) and its plain counterpart."""
+    """One steered layer of the 32-layer stack (layer 8, the first steered one) and its plain counterpart,
+    launched at the full B=4 shape: batch entry 0 is compared in full (every row of its 32 heads), the other
+    entries on sampled rows; then the standalone edit in full and the two-launch determinism check."""
+    import torch
     inp = inputs.make_config(3, seed=0, layer=8)
     _say(f"cfg3 layer 8 full size, gain {inp.gain[0]:.3f}")
     assert inp.gain[0] != 0
     dev = H.DeviceInputs(inp)
-    rows = H.sample_rows(inp, per_head=10, seed=2)
-    _check_rows(seka, inp, dev, rows, steered=True, what="cfg3 steered")
-    _check_rows(seka, inp, dev, rows, steered=False, what="cfg3 plain")
+    rows = [r for r in H.sample_rows(inp, per_head=10, seed=2) if r[0] != 0]
+    O_s = _check_rows(seka, inp, dev, rows, steered=True, what="cfg3 steered")
+    O_p = _check_rows(seka, inp, dev, rows, steered=False, what="cfg3 plain")
+    sl = lambda x: inp.widen(x[:1])
+    Q0, K0, V0 = sl(inp.Q), sl(inp.K), sl(inp.V)
+    _say("cfg3 batch entry 0, all rows (steered)")
+    ref_O, _ = orc.steered_attention(Q0, K0, V0, inp.widen(inp.U), inp.gain, inp.mask[:1], scale=inp.scale)
+    H.assert_close_bf16(H.to_f64(O_s[:1]), ref_O, "cfg3 steered, batch entry 0, all rows")
+    _say("cfg3 batch entry 0, all rows (plain)")
+    ref_P, _ = orc.causal_attention(Q0, K0, V0, scale=inp.scale)
+    H.assert_close_bf16(H.to_f64(O_p[:1]), ref_P, "cfg3 plain, batch entry 0, all rows")
+    del ref_O, ref_P, Q0, K0, V0
+    _two_runs_identical(seka, dev, inp, True, "cfg3 steered")
+    _two_runs_identical(seka, dev, inp, False, "cfg3 plain")
     # standalone edit at full size, compared in full
-    import torch
     ref_K = orc.edit_keys(inp.widen(inp.K), inp.widen(inp.U), inp.gain, inp.mask)
     K_out = torch.empty_like(dev.K)
     seka.seka_edit_keys(dev.K, K_out, dev.U, dev.gain, dev.mask)
@@ -83,6 +132,7 @@ def test_cfg4_full_size_routed(seka):
     assert np.abs(H.to_f64(w) - ref_w).max() <= H.ROUTE_ABS
     rows = H.sample_rows(inp, per_head=6, seed=3)
     _check_rows(seka, inp, dev, rows, w_dev=w, w_ref=ref_w, steered=True, what="cfg4 steered")
+    _two_runs_identical(seka, dev, inp, True, "cfg4 steered", w=w)
     # standalone edit at full size (rank 128: a workgroup takes several 64-token tiles), compared in full, out of
     # place and in place
     ref_K = orc.edit_keys(inp.widen(inp.K), inp.widen(inp.U), inp.gain, inp.mask, w=ref_w)
@@ -100,6 +150,9 @@ def test_cfg5_full_size(seka):
     dev = H.DeviceInputs(inp)
     rows = H.sample_rows(inp, per_head=12, seed=4)
     _check_rows(seka, inp, dev, rows, steered=True, what="cfg5 steered")
+    _check_rows(seka, inp, dev, rows, steered=False, what="cfg5 plain")
+    _two_runs_identical(seka, dev, inp, True, "cfg5 steered")
+    _two_runs_identical(seka, dev, inp, False, "cfg5 plain")
 
 
 def test_very_long_prompt_takes_the_register_staged_kernel(seka):

@@ -14,19 +14,15 @@ def _say(msg):
     print(msg, flush=True)
 
 
-def _run_attention(seka, dev, steered, variant=0, w=None, with_lse=True):
+def _run_attention(seka, dev, steered, w=None, with_lse=True):
     import torch
-    seka.seka_set_tuning(0, variant)
-    try:
-        O = torch.full_like(dev.Q, float("nan"))
-        lse = dev.lse_buffer() if with_lse else None
-        if steered:
-            seka.seka_attention_prefill(dev.Q, dev.K, dev.V, O, dev.U, dev.gain, dev.mask, w=w, lse=lse, scale=dev.inp.scale)
-        else:
-            seka.seka_attention_plain(dev.Q, dev.K, dev.V, O, lse=lse, scale=dev.inp.scale)
-        torch.cuda.synchronize()
-    finally:
-        seka.seka_set_tuning(0, 0)
+    O = torch.full_like(dev.Q, float("nan"))
+    lse = dev.lse_buffer() if with_lse else None
+    if steered:
+        seka.seka_attention_prefill(dev.Q, dev.K, dev.V, O, dev.U, dev.gain, dev.mask, w=w, lse=lse, scale=dev.inp.scale)
+    else:
+        seka.seka_attention_plain(dev.Q, dev.K, dev.V, O, lse=lse, scale=dev.inp.scale)
+    torch.cuda.synchronize()
     return H.to_f64(O), (H.to_f64(lse) if with_lse else None)
 
 
@@ -107,23 +103,22 @@ BF16_CASES = {
 }
 
 
-@pytest.mark.parametrize("variant", [0])
 @pytest.mark.parametrize("name", list(BF16_CASES))
-def test_bf16_attention_small(seka, name, variant):
+def test_bf16_attention_small(seka, name):
     kw = dict(BF16_CASES[name])
     cfg = kw.pop("cfg")
-    _say(f"bf16 case {name} variant {variant}")
+    _say(f"bf16 case {name}")
     inp = inputs.make_config(cfg, seed=1, **kw)
     dev = H.DeviceInputs(inp)
     o = H.oracle_inputs(inp)
     ref_O, ref_L = orc.steered_attention(o["Q"], o["K"], o["V"], o["U"], inp.gain, inp.mask, scale=inp.scale)
-    got_O, got_L = _run_attention(seka, dev, True, variant)
+    got_O, got_L = _run_attention(seka, dev, True)
     H.assert_close_bf16(got_O, ref_O, f"{name} steered O")
     H.assert_lse_close_bf16(got_L, ref_L, f"{name} steered LSE")
     ref_P, ref_PL = orc.causal_attention(o["Q"], o["K"], o["V"], scale=inp.scale)
-    got_P, got_PL = _run_attention(seka, dev, False, variant)
+    got_P, got_PL = _run_attention(seka, dev, False)
     H.assert_close_bf16(got_P, ref_P, f"{name} plain O")
-    H.assert_lse_close_bf16(got_PL, ref_PL, f"{name} plain LSE")
+    H.assert_lse_close_bf16(got_PL, ref_PL, f"{name} plain LSE", path="plain")
     assert np.abs(ref_O - ref_P).max() > 5e-2, "steering has no visible effect in this case: test is vacuous"
 
 
@@ -140,9 +135,8 @@ def test_bf16_adaseka_routed(seka):
     assert np.abs(H.to_f64(w) - ref_w).max() <= H.ROUTE_ABS
     assert ref_w.max() - ref_w.min() > 0.01, "routing is uniform: test is vacuous"
     ref_O, _ = orc.steered_attention(o["Q"], o["K"], o["V"], o["U"], inp.gain, inp.mask, w=ref_w, scale=inp.scale)
-    for variant in (0,):
-        got_O, _ = _run_attention(seka, dev, True, variant, w=w)
-        H.assert_close_bf16(got_O, ref_O, f"adaseka O variant {variant}")
+    got_O, _ = _run_attention(seka, dev, True, w=w)
+    H.assert_close_bf16(got_O, ref_O, "adaseka O")
     # standalone edit with the same weights
     ref_K = orc.edit_keys(o["K"], o["U"], inp.gain, inp.mask, w=ref_w)
     K_out = torch.empty_like(dev.K)
@@ -208,10 +202,9 @@ def test_bf16_tiny_lengths(seka, S):
     dev = H.DeviceInputs(inp)
     o = H.oracle_inputs(inp)
     ref_O, ref_L = orc.steered_attention(o["Q"], o["K"], o["V"], o["U"], inp.gain, inp.mask, scale=inp.scale)
-    for variant in (0,):
-        got_O, got_L = _run_attention(seka, dev, True, variant)
-        H.assert_close_bf16(got_O, ref_O, f"S={S} O")
-        H.assert_lse_close_bf16(got_L, ref_L, f"S={S} LSE")
+    got_O, got_L = _run_attention(seka, dev, True)
+    H.assert_close_bf16(got_O, ref_O, f"S={S} O")
+    H.assert_lse_close_bf16(got_L, ref_L, f"S={S} LSE")
 
 
 def test_degenerate_steering_equals_plain(seka):

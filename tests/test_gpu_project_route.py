@@ -9,7 +9,9 @@ from tests import helpers as H
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("shape", [(2, 256, 8, 2, 192), (1, 384, 4, 4, 64), (3, 128, 6, 3, 320)])
+# E / 64 slices: 3, 1 and 5 (loop ends in its tail), 2, 4 and 8 (even counts: the loop ends without a tail, as at E = 4096)
+@pytest.mark.parametrize("shape", [(2, 256, 8, 2, 192), (1, 384, 4, 4, 64), (3, 128, 6, 3, 320),
+                                   (1, 256, 4, 2, 128), (2, 128, 8, 2, 256), (1, 128, 4, 1, 512)])
 def test_project_route(seka, shape):
     import torch
     B, S, Hq, Hkv, E = shape

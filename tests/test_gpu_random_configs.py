@@ -69,10 +69,51 @@ def test_random_configuration(seka, case):
         H.assert_lse_close_bf16(got_L[b:b + 1, :, :n], ref_L, f"case {case} prompt {b} LSE")
 
 
+def _first_order_bounds(o, K_edit, ref_O, mask, scale, G, kappa=6.0):
+    """Per output row (b, hq, i): how far the bf16 kernel may land from the exact result, to first order, from
+    the oracle's own probabilities.  Error model: an edited key is rounded to bf16 before scoring and its subspace
+    coordinates before the second product (two roundings of relative size up to 2^-8, standard deviation
+    2^-8 / sqrt(3) each), so the score of a highlighted key j carries an error ds_ij of variance
+    sig_ij^2 = 2 (scale 2^-8)^2 / 3 * sum_d q_id^2 k'_jd^2; every probability is rounded to bf16 for the PV
+    product and the row sum (relative variance (2^-8)^2 / 3).  The softmax turns these into
+    dO_i = sum_j p_ij (ds_ij + dp_ij) (v_j - O_i) and dLSE_i = sum_j p_ij (ds_ij + dp_ij), sums of independent terms:
+    the bounds are kappa standard deviations of those sums (largest over the d components for O).
+    Returns (bound_O[B,Hq,T], bound_LSE[B,Hq,T], P[B,Hq,T,T] for diagnostics)."""
+    Q, V = o["Q"], o["V"]
+    B, T, Hq, d = Q.shape
+    bO = np.empty((B, Hq, T))
+    bL = np.empty((B, Hq, T))
+    P_all = np.empty((B, Hq, T, T))
+    vis = np.tril(np.ones((T, T), dtype=bool))
+    rel2 = (2.0 ** -8) ** 2 / 3.0
+    for b in range(B):
+        hl = (np.asarray(mask[b]) != 0).astype(np.float64)
+        for hq in range(Hq):
+            h = hq // G
+            A = np.where(vis, scale * (Q[b, :, hq] @ K_edit[b, :, h].T), -np.inf)
+            P = np.exp(A - A.max(axis=1, keepdims=True))
+            P /= P.sum(axis=1, keepdims=True)
+            sig2 = 2.0 * scale ** 2 * rel2 * ((Q[b, :, hq] ** 2) @ (K_edit[b, :, h] ** 2).T) * hl[None, :]
+            W = P ** 2 * (sig2 + rel2)                               # variance carried by key j in row i
+            Vh, Oi = V[b, :, h], ref_O[b, :, hq]
+            var = W @ (Vh ** 2) - 2.0 * Oi * (W @ Vh) + Oi ** 2 * W.sum(axis=1, keepdims=True)   # sum_j W_ij (v_jd - O_id)^2
+            bO[b, hq] = kappa * np.sqrt(np.maximum(var, 0.0).max(axis=1))
+            bL[b, hq] = kappa * np.sqrt(W.sum(axis=1))
+            P_all[b, hq] = P
+    return bO, bL, P_all
+
+
 @pytest.mark.parametrize("mult", [0.02, 3.0, 6.0])
 def test_score_scales(seka, mult):
     """Nearly flat and very sharp softmax rows (scores ~ mult^2 * N(0, 1) * sqrt(D) * scale): the reference exponent
-    of the online softmax is raised late and in jumps of any size, rows are dominated by one key or by none."""
+    of the online softmax is raised late and in jumps of any size, rows are dominated by one key or by none.
+
+    With inputs scaled by 6 the scores have a standard deviation of 36 and a highlighted key's bf16 rounding moves
+    its score by up to a few tenths: where two keys compete for a row, that shifts weight between two V rows of
+    magnitude ~20, so single outputs move by several units although every step is as accurate as bf16 allows.
+    The check is therefore per row: |dO| and |dLSE| must stay within six standard deviations of the first-order
+    error model computed from the oracle's own probabilities (a wrong key, a wrong weight or a lost rescale moves O
+    by ~|V| on every row, and most rows' bounds are a small fraction of that, which the test also asserts)."""
     import torch
     print(f"score scale: inputs x {mult}", flush=True)
     inp = inputs.make_layer("scales", "bf16", B=2, S=700, Hq=8, Hkv=2, D=128, M=1, r=32, gain=1.0,
@@ -86,10 +127,26 @@ def test_score_scales(seka, mult):
     ref_O, ref_L = orc.steered_attention(o["Q"], o["K"], o["V"], o["U"], inp.gain, inp.mask, scale=inp.scale)
     got_O, got_L = H.to_f64(O), H.to_f64(lse)
     assert np.isfinite(got_O).all() and np.isfinite(got_L).all()
-    # outputs are convex combinations of V rows, so the absolute bound scales with the inputs; a sharp row moves
-    # by one key's bf16 score error times its weight, which the bound for unit inputs covers after that scaling
-    s = max(1.0, mult)
-    d = np.abs(got_O - ref_O)
-    assert d.max() <= H.BF16_MAX * s * max(1.0, mult ** 2), f"max |dO| {d.max():.4g}"
-    assert d.mean() <= H.BF16_MEAN * s * max(1.0, mult ** 2), f"mean |dO| {d.mean():.4g}"
-    print(f"mult {mult}: max |dO| {d.max():.4g} mean {d.mean():.4g}; max |dLSE| {np.abs(got_L - ref_L).max():.4g}", flush=True)
+    K_edit = orc.edit_keys(o["K"], o["U"], inp.gain, inp.mask)
+    bO, bL, P = _first_order_bounds(o, K_edit, ref_O, inp.mask, inp.scale, inp.Hq // inp.Hkv)
+    dO = np.abs(got_O - ref_O).max(axis=3).transpose(0, 2, 1)          # [B,Hq,T]
+    dL = np.abs(got_L - ref_L)
+    vscale = float(np.abs(o["V"]).max())
+    # six standard deviations of the first-order model + the output's own bf16 rounding + an fp32 floor
+    limO = bO + 2.0 ** -8 * np.abs(ref_O).max(axis=3).transpose(0, 2, 1) + 1e-4 * vscale
+    limL = bL + 1e-4
+    okO, okL = dO <= limO, dL <= limL
+    b_, h_, i_ = np.unravel_index(np.argmax(dO / limO), dO.shape)
+    top = np.argsort(P[b_, h_, i_])[-2:][::-1]
+    print(f"mult {mult}: max |dO| {dO.max():.4g} (mean {np.abs(got_O - ref_O).mean():.4g}), max |dLSE| {dL.max():.4g}; "
+          f"largest |dO| / bound {np.max(dO / limO):.3g}, |dLSE| / bound {np.max(dL / limL):.3g}; "
+          f"median row bound {np.median(limO):.4g} vs max|V| {vscale:.3g}; tightest row (b={b_}, hq={h_}, i={i_}): "
+          f"|dO| {dO[b_, h_, i_]:.4g}, bound {limO[b_, h_, i_]:.4g}, top keys {top.tolist()} with p "
+          f"{P[b_, h_, i_, top].round(4).tolist()}, highlighted {inp.mask[b_, top].tolist()}", flush=True)
+    assert okO.all(), f"{(~okO).sum()} rows exceed their first-order bound on O"
+    assert okL.all(), f"{(~okL).sum()} rows exceed their first-order bound on LSE"
+    # the bound must mean something: on most rows it is a small fraction of what a wrong key or weight would cost
+    assert np.median(limO) < 0.02 * vscale, "row bounds are too loose to detect a wrong kernel"
+    if mult <= 1.0:
+        H.assert_close_bf16(got_O, ref_O, f"mult {mult} O")
+        H.assert_lse_close_bf16(got_L, ref_L, f"mult {mult} LSE")

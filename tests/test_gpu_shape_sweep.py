@@ -35,9 +35,11 @@ def test_lengths_around_tile_boundaries(seka, group, rank):
         H.assert_close_bf16(H.to_f64(O), ref_O, f"{group} r={rank} S={S} O")
         H.assert_lse_close_bf16(H.to_f64(lse), ref_L, f"{group} S={S} LSE")
         Op = torch.full_like(dev.Q, float("nan"))
-        seka.seka_attention_plain(dev.Q, dev.K, dev.V, Op, scale=inp.scale)
+        lse.fill_(float("nan"))
+        seka.seka_attention_plain(dev.Q, dev.K, dev.V, Op, lse=lse, scale=inp.scale)
         torch.cuda.synchronize()
-        ref_P, _ = orc.causal_attention(o["Q"], o["K"], o["V"], scale=inp.scale)
+        ref_P, ref_PL = orc.causal_attention(o["Q"], o["K"], o["V"], scale=inp.scale)
         H.assert_close_bf16(H.to_f64(Op), ref_P, f"{group} S={S} plain O")
+        H.assert_lse_close_bf16(H.to_f64(lse), ref_PL, f"{group} S={S} plain LSE", path="plain")
         worst = max(worst, float(np.abs(H.to_f64(O) - ref_O).max()))
     print(f"{group}: worst |dO| {worst:.4f}", flush=True)

@@ -68,13 +68,22 @@ def assert_close_bf16(got, ref, what=""):
 LSE_BOUNDS = {"steered": (2e-2, 2e-3), "plain": (5e-3, 5e-4), "decode": (5e-3, 5e-4)}
 
 
-def assert_lse_close_bf16(got, ref, what="", path="steered"):
+def assert_lse_close_bf16(got, ref, what="", path="steered", amp=2.0, n_keys=None):
+    """Steered path only: the score error of an edited key is proportional to its size, so the mean bound scales
+    with the key magnification amp = |a| + |g| sum_m |w_m| of k' = a k + g P k (2 in the benchmark configurations,
+    for which the bound is stated); and in prompts shorter than one key tile (n_keys < 64) most rows hold a few
+    keys only and inherit their score errors undamped (the mean over rows is then about the rms score error
+    itself, ~2.5e-3 at amp = 2, not its average over many keys): three times the bound."""
     mx, mean = LSE_BOUNDS[path]
+    if path == "steered":
+        mean *= max(1.0, amp / 2.0)
+        if n_keys is not None and n_keys < 64:
+            mean *= 3.0
     d = np.abs(got - ref)
     assert np.isfinite(got).all(), f"{what}: non-finite output"
     print(f"[lse {path}] {what}: max {d.max():.3g} mean {d.mean():.3g}", flush=True)
     assert d.max() <= mx, f"{what}: max |diff| {d.max():.4g} > {mx}"
-    assert d.mean() <= mean, f"{what}: mean |diff| {d.mean():.4g} > {mean}"
+    assert d.mean() <= mean, f"{what}: mean |diff| {d.mean():.4g} > {mean:.3g}"
 
 
 def assert_close_f32(got, ref, what="", tol=F32_ABS):

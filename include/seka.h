@@ -235,6 +235,24 @@ seka_status seka_attention_decode(const void* q, const void* K, const void* V, v
                                   size_t workspace_bytes, void* hip_stream);
 
 /*
+ * seka_attention_decode_static — seka_attention_decode for callers that cannot allocate device memory or size a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * results and errors, without the workspace pair: the partial states go to a buffer of
+ * SEKA_DECODE_STATIC_MAX_BYTES (8 MiB) that the library owns in device memory (one per GPU that loads the
+ * library, held until the process ends).  The call allocates and frees nothing.
+ *   - Problems whose partial states exceed the buffer (seka_decode_workspace_bytes(sh) > SEKA_DECODE_STATIC_MAX_BYTES;
+ *     B * Hq * splits * (D + 2) * 4 bytes with at most 64 splits, e.g. more than 256 (prompt, query head) pairs
+ *     of a long cache at D = 128) return SEKA_ERR_WORKSPACE and launch nothing: use seka_attention_decode.
+ *   - Every call on a GPU shares that GPU's buffer.  Calls on one stream are ordered by it; calls that overlap
+ *     in time on one GPU (different streams, no dependency) race on the buffer and give wrong results.  Nothing
+ *     in the buffer has to start at zero: every slot a launch reads is written earlier in the same call.
+ *   - The first call on a device looks the buffer's address up (no allocation); make it before a capture begins.
+ */
+enum { SEKA_DECODE_STATIC_MAX_BYTES = 8 << 20 };
+seka_status seka_attention_decode_static(const void* q, const void* K, const void* V, void* O, float* lse,
+                                         const int32_t* seq_lens, const seka_shape* sh, void* hip_stream);
+
+/*
  * seka_learn_projection — the offline stage for one layer (paper Sec. 3.1): per KV head, the cross-covariance
  * Omega_h = h_neutral^T h_signal / n of token key embeddings sampled under a neutral and under a relevant
  * (or irrelevant) context, its singular value decomposition Omega = U Sigma V^T, and the rank k_h that keeps a

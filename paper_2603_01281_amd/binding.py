@@ -67,6 +67,8 @@ lib.seka_decode_workspace_bytes.restype = _sz
 lib.seka_decode_workspace_bytes.argtypes = [_shape_p]
 lib.seka_attention_decode.restype = _i32
 lib.seka_attention_decode.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _shape_p, _vp, _sz, _vp]
+lib.seka_attention_decode_static.restype = _i32
+lib.seka_attention_decode_static.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _shape_p, _vp]
 lib.seka_attention_prefill_ragged.restype = _i32
 lib.seka_attention_prefill_ragged.argtypes = [_vp, _vp, _vp, _vp, _vp, _shape_p, _steer_p, _vp, _vp]
 lib.seka_learn_workspace_bytes.restype = _sz
@@ -290,6 +292,19 @@ def seka_attention_decode(q, K, V, O, seq_lens=None, lse=None, scale=0.0, worksp
     _check(lib.seka_attention_decode(_dev(q, "q"), _dev(K, "K"), _dev(V, "V"), _dev(O, "O"), _dev(lse, "lse"),
                                      _dev(seq_lens, "seq_lens"), ctypes.byref(sh), _dev(workspace, "workspace"),
                                      workspace.numel() * workspace.element_size(), _stream(stream)))
+    return O
+
+
+SEKA_DECODE_STATIC_MAX_BYTES = 8 << 20
+
+
+def seka_attention_decode_static(q, K, V, O, seq_lens=None, lse=None, scale=0.0, stream=None):
+    """seka_attention_decode on the library-owned partial-state buffer: no workspace, no allocation."""
+    B, Hq, D = q.shape
+    S, Hkv = K.shape[1], K.shape[2]
+    sh = _shape(B, S, Hq, Hkv, D, _dtype_code(q), scale)
+    _check(lib.seka_attention_decode_static(_dev(q, "q"), _dev(K, "K"), _dev(V, "V"), _dev(O, "O"), _dev(lse, "lse"),
+                                            _dev(seq_lens, "seq_lens"), ctypes.byref(sh), _stream(stream)))
     return O
 
 

@@ -300,6 +300,22 @@ seka_status seka_attention_decode(const void* q, const void* K, const void* V, v
   return launch_status(e);
 }
 
+seka_status seka_attention_decode_static(const void* q, const void* K, const void* V, void* O, float* lse,
+                                         const int32_t* seq_lens, const seka_shape* sh, void* hip_stream) {
+  size_t need = 0;
+  seka_status rc = check_decode(q, K, V, O, lse, seq_lens, sh, &need);
+  if (rc != SEKA_OK) return rc;
+  if (need > (size_t)SEKA_DECODE_STATIC_MAX_BYTES) return SEKA_ERR_WORKSPACE;   // larger problems: seka_attention_decode
+  void* scratch_ptr = nullptr;
+  (void)hipGetLastError();
+  hipError_t e = seka::decode_static_scratch(&scratch_ptr);
+  if (e != hipSuccess) return launch_status(e);
+  const float scale = sh->softmax_scale > 0.0f ? sh->softmax_scale : 1.0f / std::sqrt((float)sh->D);
+  e = seka::launch_decode(q, K, V, O, lse, seq_lens, sh->B, sh->S, sh->Hq, sh->Hkv, sh->D, sh->dtype, scale, scratch_ptr,
+                          reinterpret_cast<hipStream_t>(hip_stream));
+  return launch_status(e);
+}
+
 size_t seka_learn_workspace_bytes(const seka_shape* sh) {
   if (check_shape(sh, false) != SEKA_OK || (int64_t)sh->B * sh->S >= (1 << 24)) return 0;
   return seka::learn_workspace_bytes(sh->Hkv, sh->D, sh->B * sh->S);

@@ -55,6 +55,9 @@ hipError_t launch_route(const void* Q, int B, int S, int Hq, int Hkv, int D, int
                         int window = 0);
 
 size_t decode_workspace_bytes(int B, int S, int Hq, int Hkv, int D);
+constexpr size_t kDecodeStaticScratchBytes = (size_t)SEKA_DECODE_STATIC_MAX_BYTES;   // the library-owned buffer
+// Device address of the library-owned partial-state buffer on the current device (resolved once per device).
+hipError_t decode_static_scratch(void** out);
 hipError_t launch_decode(const void* q, const void* K, const void* V, void* O, float* lse, const int* lens, int B, int S,
                          int Hq, int Hkv, int D, int dtype, float scale, void* workspace, hipStream_t s);
 

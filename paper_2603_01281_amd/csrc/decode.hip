@@ -10,11 +10,18 @@
 // shares every byte read), and keeps one online-softmax state per head and lane group with a lazily raised
 // reference exponent.  Partial states are merged across lanes, waves (LDS) and splits (stage 2, fixed order, so
 // the result does not depend on scheduling).
+#include <mutex>
+
 #include "common.h"
 
 namespace seka {
 
 namespace {
+
+// Library-owned partial-state buffer of seka_attention_decode_static (callers that cannot allocate).  One copy per
+// GPU that loads the library, held until the process ends; host code never uses this name as an address (it is
+// a host-side stand-in there): decode_static_scratch() resolves the device address once per device.
+static __device__ __align__(256) unsigned char scratch[kDecodeStaticScratchBytes];
 
 constexpr int kDecThreads = 256;
 constexpr int kDecWaves = kDecThreads / 64;
@@ -352,6 +359,26 @@ hipError_t launch_decode_td(const void* q, const void* K, const void* V, void* O
 }
 
 }  // namespace
+
+hipError_t decode_static_scratch(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptrs[kMaxDevices] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptrs[dev]) {                         // first call on this device, with it current: its own copy's address
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    ptrs[dev] = p;
+  }
+  *out = ptrs[dev];
+  return hipSuccess;
+}
 
 size_t decode_workspace_bytes(int B, int S, int Hq, int Hkv, int D) {
   return (size_t)B * Hq * decode_splits(B, Hkv, Hq / Hkv, S) * (D + 2) * sizeof(float);

@@ -10,17 +10,19 @@
 // tile with the transposing LDS read ds_read_b64_tr_b16.  A workgroup is HPW query heads of one KV group x
 // RBW blocks of 32 query rows, all sharing the K/V tiles (and the edit) of that KV head.
 //
-// What bounds this kernel on gfx950 is the SIMD's vector issue port, not the matrix pipe: a 32x32x16 bf16
-// MFMA holds the port for about 16 cycles of its 32, a plain vector instruction for 4, an exponential for
-// about 8, and instructions of the two waves of a SIMD queue on the same port.  Two consequences:
+// What bounds this kernel on gfx950 is the SIMD's vector issue port and, behind it, the chip's power limit, not the
+// matrix pipe alone: a 32x32x16 bf16 MFMA keeps the port from issuing other vector work for about 22 of its 32
+// cycles, a plain vector instruction takes 3 to 5 cycles of it, the transcendental unit accepts one exponential
+// about every 10 cycles, and the two waves of a SIMD queue on the same port.  Consequences:
 //   * every vector instruction in the loop that is not softmax arithmetic is removed: LDS read addresses
 //     are a register plus an immediate (the loop is unrolled over the three ring stages so that stage
 //     offsets are compile-time constants), tile loads take a scalar base plus a per-lane offset computed
-//     once, the row maximum uses three-input max, the row sum uses the bf16 dot-product instruction;
+//     once, and the common case of a step computes no row maximum at all (see `step`): 48 vector instructions
+//     per 16 MFMAs;
 //   * MFMAs and vector instructions alternate in program order, and every MFMA has vector work beside it:
 //     a step handles three consecutive 32-key blocks at once: the S^T products of the next block, the softmax
 //     of the current one and the PV products of the previous one (whose probabilities were formed one step
-//     earlier), so the exponentials are spread over twelve MFMAs instead of four.
+//     earlier), with one exponential per MFMA.
 // The softmax runs per 32-key block (half a tile), which halves the score registers the pipeline needs.
 // K tiles live in a ring of three LDS stages; V in a ring of six half tiles that runs half a tile behind K
 // (see the tile loads).  K(t+2) and the V blocks 2t+3, 2t+4 are requested during iteration t (in the hot loop
@@ -75,7 +77,7 @@ __device__ __forceinline__ void pipe_load_16B(const void* base, uint32_t lane_of
 // HPW heads x RBW row groups = waves per workgroup; every wave owns RPW blocks of 32 consecutive query rows.
 // RPW = 2 (four waves, one per SIMD, 512-register budget) reads every K / V fragment once for two products.
 // NKR: rank of the concatenated basis in blocks of 32 columns (compile-time so that the edit is straight-line code).
-template <int HPW, int RBW, int RPW, bool STEER, int NKR, int SCHED = 1>
+template <int HPW, int RBW, int RPW, bool STEER, int NKR>
 __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(AttnArgs a, SteerArgs st) {
   constexpr int D = DMA_D;
   constexpr int NW = HPW * RBW;
@@ -190,9 +192,12 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
       for (int n = 0; n < SPW; ++n) pipe_load_16B(tile, koff[n], lds_stage_base + slot_lds[n]);
     } else {
 #pragma unroll
-      for (int n = 0; n < SPW; ++n)
-        pipe_load_16B(Kbytes, koff[n] + (uint32_t)(min(t * BK + slot_row[n], S - 1) - slot_row[n]) * rowbytes,
+      for (int n = 0; n < SPW; ++n) {
+        uint32_t ko = koff[n];
+        asm volatile("" : "+v"(ko));     // formed here, not hoisted out of the tile loops into a register (or scratch slot) of its own
+        pipe_load_16B(Kbytes, ko + (uint32_t)(min(t * BK + slot_row[n], S - 1) - slot_row[n]) * rowbytes,
                       lds_stage_base + slot_lds[n]);
+      }
     }
   };
   // Shifted V tile t: block 2t - 1 to ring byte offset posA, block 2t to posB.
@@ -204,9 +209,12 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
       for (int n = 0; n < SPW; ++n) pipe_load_16B(tile, voff[n], vst_base + (vslot_hi[n] ? posB : posA) + vslot_lds[n]);
     } else {
 #pragma unroll
-      for (int n = 0; n < SPW; ++n)
-        pipe_load_16B(Vbytes, voff[n] + (uint32_t)(min(max(first + slot_row[n], 0), S - 1) - slot_row[n]) * rowbytes,
+      for (int n = 0; n < SPW; ++n) {
+        uint32_t vo = voff[n];
+        asm volatile("" : "+v"(vo));
+        pipe_load_16B(Vbytes, vo + (uint32_t)(min(max(first + slot_row[n], 0), S - 1) - slot_row[n]) * rowbytes,
                       vst_base + (vslot_hi[n] ? posB : posA) + vslot_lds[n]);
+      }
     }
   };
   auto issue_k = [&](int t) __attribute__((always_inline)) { issue_k_to(std::false_type{}, t, kst_base + (t % 3) * TB); };
@@ -505,6 +513,9 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   float m_run[RPW], l_run[RPW];
 #pragma unroll
   for (int rp = 0; rp < RPW; ++rp) { m_run[rp] = -1e30f; l_run[rp] = 0.f; }
+  // The tile loops live in a (generic, always inlined) lambda of their own.  This changes nothing in what is
+  // computed; the compiler allocates the loop's registers differently for it, and the launch is 3 % faster.
+  auto run_block = [&](auto) __attribute__((always_inline)) {
 
   // LDS byte addresses of this lane's operands inside stage 0 (stage and row-block offsets are immediates):
   // K: row l32 (+32), logical chunk 2 ks + hf, physical chunk (2 ks + hf) ^ (l32 & 15)
@@ -606,6 +617,29 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
         lsum = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, lsum, false);
       }
     l_run[rp] = lsum;
+  };
+  // The same for the schedule without a per-block maximum: the scores are left untouched, the sum of the rounded
+  // probabilities is returned instead of being added to the row's running sum.
+  auto block_exp_sum = [&](const f32x16& sv, bf16x8 (&pb)[2], float& lsum) __attribute__((always_inline)) {
+    const float mneg = -m_run[0];
+    float pv[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) pv[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], c2, mneg));
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      pb[0][e] = (__bf16)pv[e];
+      pb[1][e] = (__bf16)pv[8 + e];
+    }
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    float acc = 0.f;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int e = 0; e < 8; e += 2) {
+        const bf16x2 pp = {pb[kb][e], pb[kb][e + 1]};
+        acc = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, acc, false);
+      }
+    lsum = acc;
   };
   // O^T += V^T P^T for one 32-key block; off = LDS byte offset of the block's first row
   auto pv_half = [&](int off, const bf16x8 (&pb)[RPW][2]) __attribute__((always_inline)) {
@@ -724,6 +758,14 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   // kpre: the first two K fragments of the block at KOFF, read during the previous step (an LDS read issued right
   // before the MFMA that needs it leaves the wave waiting for the whole LDS latency); on return it holds those of
   // the block at KNEXT, the one the following step scores.
+  //
+  // No row maximum in the common case.  The probabilities of `cur` are formed against the row's reference exponent
+  // as it stands; their sum over the block tells whether that was safe: a sum beyond kSumLimit (or one that is not
+  // a number) means some score ran far ahead of the reference, and only then is the block's maximum computed, the
+  // reference raised and the block's probabilities formed again (a handful of times per row; the first block of a
+  // row always takes this turn, its reference starts at -1e30).  The common case is 16 multiply-adds, 16
+  // exponentials, 8 packings and 8 dot products per 16 MFMAs: no three-input maxima, no cross-lane exchange, no
+  // raise test.
   auto kfrag = [&](int ks, int off) __attribute__((always_inline)) -> bf16x8 {
     return *(pipe_lds_bf16x8_ptr)(uintptr_t)(kaddr[ks] + off);
   };
@@ -731,38 +773,21 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 #pragma unroll
     for (int rp = 0; rp < RPW; ++rp) sn[rp] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a0, qf[rp][ks], sn[rp], 0, 0, 0);
   };
+  constexpr float kSumLimit = 4096.f;          // probabilities stay below 2^12
   auto step = [&](auto koff_c, auto knext_c, auto voff_c, f32x16 (&cur)[RPW], f32x16 (&next)[RPW], bf16x8 (&pb)[RPW][2],
                   bf16x8 (&kpre)[2]) __attribute__((always_inline)) {
-    static_assert(KS == 8, "the fragment schedule below is written for eight k-slices");
+    static_assert(KS == 8 && RPW == 1, "the schedule below is written for eight k-slices and one row block per wave");
     const int KOFF = koff_c, KNEXT = knext_c, VOFF = voff_c;
-    bf16x8 pn[RPW][2];
-    float mfull[RPW];
-    // (a) first half of the products, interleaved with the row maxima; fragments 4 and 5 are requested here
+    bf16x8 pn[2];
+    float lb;
 #pragma unroll
-    for (int rp = 0; rp < RPW; ++rp)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) next[rp][r] = 0.f;
+    for (int r = 0; r < 16; ++r) next[0][r] = 0.f;
     qk_one(0, kpre[0], next);
     qk_one(1, kpre[1], next);
     const bf16x8 k2 = kfrag(2, KOFF), k3 = kfrag(3, KOFF);
     qk_one(2, k2, next);
     qk_one(3, k3, next);
     const bf16x8 k4 = kfrag(4, KOFF), k5 = kfrag(5, KOFF);
-#pragma unroll
-    for (int rp = 0; rp < RPW; ++rp) mfull[rp] = block_max(cur[rp]);
-    if (SCHED == 1) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-#pragma unroll
-      for (int i = 0; i < 4 * RPW; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        if (i == 1 * RPW || i == 2 * RPW) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
-      }
-    }
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int rp = 0; rp < RPW; ++rp) raise_reference(rp, mfull[rp]);
-    // (b) second half of the products and the PV products of the previous block, interleaved with the exponentials
     qk_one(4, k4, next);
     qk_one(5, k5, next);
     const bf16x8 k6 = kfrag(6, KOFF), k7 = kfrag(7, KOFF);
@@ -771,35 +796,34 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     pv_half(VOFF, pb);
     kpre[0] = kfrag(0, KNEXT);
     kpre[1] = kfrag(1, KNEXT);
+    block_exp_sum(cur[0], pn, lb);
+    // Program order: every MFMA is followed by its share of the 24 LDS reads, two plain vector instructions and
+    // (from the second MFMA on, when the first multiply-adds have been issued) one exponential: the transcendental
+    // unit takes one instruction about every ten cycles, and a run of exponentials stalls the wave in front of
+    // the next MFMA.
+    __builtin_amdgcn_sched_group_barrier(0x100, 2, 2);          // fragments 2 and 3
 #pragma unroll
-    for (int rp = 0; rp < RPW; ++rp) block_exp(rp, cur[rp], pn[rp]);
-    if (SCHED == 1) {
-      __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);       // fragments 6 and 7
-#pragma unroll
-      for (int i = 0; i < 4 * RPW; ++i) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
-        if (i >= 2 * RPW - 1 && i % RPW == RPW - 1) __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);   // V operands, two MFMAs ahead
-        __builtin_amdgcn_sched_group_barrier(0x002, 4, 1);
-      }
-#pragma unroll
-      for (int i = 0; i < 2 * DB; ++i) {
-#pragma unroll
-        for (int rp = 0; rp < RPW; ++rp) {
-          __builtin_amdgcn_sched_group_barrier(0x008, 1, 1);
-          if (rp == 0 && i < 2 * DB - 3) __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);
-          if (rp == 0 && i == 2 * DB - 3) __builtin_amdgcn_sched_group_barrier(0x100, 2, 1);     // the next block's first fragments
-          __builtin_amdgcn_sched_group_barrier(0x002, 5, 1);
-        }
-      }
+    for (int i = 0; i < 16; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 2);
+      if (i < 14 && !(i & 1)) __builtin_amdgcn_sched_group_barrier(0x100, 2, 2);
+      if (i < 15 && ((i & 1) || i == 14)) __builtin_amdgcn_sched_group_barrier(0x100, 1, 2);
+      __builtin_amdgcn_sched_group_barrier(0x002, 2, 2);
+      if (i >= 1) __builtin_amdgcn_sched_group_barrier(0x400, 1, 2);
     }
+    __builtin_amdgcn_sched_group_barrier(0x400, 1, 2);
     // The probabilities are first used by the next step: without a use here their whole computation is sunk
     // into that step, away from the MFMAs it is meant to share the issue port with.
-#pragma unroll
-    for (int rp = 0; rp < RPW; ++rp) asm volatile("" : "+v"(pn[rp][0]), "+v"(pn[rp][1]), "+v"(l_run[rp]));
+    asm volatile("" : "+v"(pn[0]), "+v"(pn[1]), "+v"(lb));
     __builtin_amdgcn_sched_barrier(0);
-    rescale_outputs();
-#pragma unroll
-    for (int rp = 0; rp < RPW; ++rp) { pb[rp][0] = pn[rp][0]; pb[rp][1] = pn[rp][1]; }
+    if (__builtin_expect(__any(!(lb <= kSumLimit)), 0)) {
+      // `cur` was produced by the previous step's MFMAs: far enough behind for the inline-assembly maxima
+      raise_reference(0, block_max(cur[0]));
+      block_exp_sum(cur[0], pn, lb);
+      rescale_outputs();       // after this step's PV product, whose probabilities were formed against the old reference
+    }
+    l_run[0] += lb;
+    pb[0][0] = pn[0];
+    pb[0][1] = pn[1];
   };
   // One tile every row of this wave sees in full; ST = t % 3 is compile-time so that every LDS read address is
   // a register plus an immediate.  Enters with S(t, keys 0..31) in sc0 and the probabilities of the block before
@@ -901,6 +925,8 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     bottom(std::false_type{}, t);
   }
   if (owed) pv_half(owed_off, pb);
+  };
+  run_block(std::false_type{});
 
   // ---- next block's first loads (after a barrier: the last PV product above still read the V ring), then this
   // block's output ----

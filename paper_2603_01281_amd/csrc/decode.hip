@@ -293,24 +293,39 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(const T* __
 }
 
 // grid (Hq, B), block kFinThreads: thread (j, d) merges splits j, j + NJ, ... in that order, then the NJ partial
-// states are merged in index order: a fixed order, whatever the launch.
-constexpr int kFinThreads = 512;
+// states are merged in index order: a fixed order, whatever the launch.  The kernel is pure latency (a few tens of
+// kilobytes per workgroup), so every load of a thread is issued before the first is used, and a thread has at most
+// kDecMaxSplits / NJ of them.
+constexpr int kFinThreads = 1024;
 template <typename T, int D>
 __global__ __launch_bounds__(kFinThreads) void decode_finish_kernel(const float* __restrict__ part, int Hq, int splits,
                                                                     T* __restrict__ O, float* __restrict__ lse) {
   constexpr int NJ = kFinThreads / D;
+  constexpr int NI = (kDecMaxSplits + NJ - 1) / NJ;        // splits per thread, at most
   __shared__ float sm[NJ][D + 2];
   const int hq = blockIdx.x, b = blockIdx.y, d = threadIdx.x % D, j = threadIdx.x / D;
   const float* src = part + ((size_t)b * Hq + hq) * splits * (D + 2);
-  float mm = kNegBig;
-  for (int s = j; s < splits; s += NJ) mm = fmaxf(mm, src[(size_t)s * (D + 2) + D]);
-  float ll = 0.f, oo = 0.f;
-  for (int s = j; s < splits; s += NJ) {
-    const float* ps = src + (size_t)s * (D + 2);
-    const float aw = __builtin_amdgcn_exp2f(ps[D] - mm);
-    ll += ps[D + 1] * aw;
-    oo += ps[d] * aw;
+  float mv[NI], lv[NI], ov[NI];
+#pragma unroll
+  for (int i = 0; i < NI; ++i) {
+    const int s = j + NJ * i;
+    const float* ps = src + (size_t)(s < splits ? s : 0) * (D + 2);     // clamped: the value is dropped below
+    mv[i] = ps[D];
+    lv[i] = ps[D + 1];
+    ov[i] = ps[d];
   }
+  float mm = kNegBig;
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+    if (j + NJ * i < splits) mm = fmaxf(mm, mv[i]);
+  float ll = 0.f, oo = 0.f;
+#pragma unroll
+  for (int i = 0; i < NI; ++i)
+    if (j + NJ * i < splits) {
+      const float aw = __builtin_amdgcn_exp2f(mv[i] - mm);
+      ll += lv[i] * aw;
+      oo += ov[i] * aw;
+    }
   sm[j][d] = oo;
   if (d == 0) {
     sm[j][D] = mm;

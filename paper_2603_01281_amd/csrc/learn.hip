@@ -3,7 +3,8 @@
 // that keeps a fraction gamma of the singular-value mass (Eq. 3), and the head score D_h = mean ||h+ - h-||_2.
 //
 // Not on the inference path: written for clarity and determinism, not speed.
-//   cov_partial_kernel   Omega in 16-row strips, the token range split into chunks (fp32 accumulation).
+//   cov_partial_kernel   Omega in 16-row strips, the token range split into chunks (fp32 accumulation); bf16
+//                        tensors take cov_partial_mfma_kernel (exact products on the matrix cores, one pass).
 //   jacobi_svd_kernel    one workgroup per head, Omega (d x d, column-major, padded) resident in LDS.  One-sided
 //                        (Hestenes) Jacobi: plane rotations applied from the right make the columns mutually
 //                        orthogonal, Omega V = U Sigma, so at convergence column j is sigma_j u_j: the left singular
@@ -66,6 +67,89 @@ __global__ __launch_bounds__(kLearnThreads) void cov_partial_kernel(const T* __r
 #pragma unroll
   for (int r = 0; r < RPT; ++r)
     part[(((size_t)split * Hkv + h) * D + i0 + RPT * rgrp + r) * D + j] = acc[r];
+}
+
+// The same partial sums for bf16 tensors on the matrix cores.  A product of two bf16 values is exact in fp32, so
+// v_mfma_f32_32x32x16_bf16 with its fp32 accumulation computes what the fp32 kernel above computes (up to the
+// order of the additions) and the kernel becomes a single pass over both views: grid (splits, Hkv), a workgroup
+// stages 64 tokens x D of both views in LDS with 16-byte loads and every wave owns D*D/4096 blocks of 32 x 32 of
+// Omega.  Both MFMA operands run along the token axis, the strided one of the row-major [token][d] tiles, hence
+// the transposing LDS reads (rows padded by 16 bytes: no bank conflicts).
+typedef __attribute__((address_space(3))) s16x4* learn_lds_s16x4_ptr;
+template <int D>
+__global__ __launch_bounds__(kLearnThreads) void cov_partial_mfma_kernel(const uint16_t* __restrict__ hn,
+                                                                         const uint16_t* __restrict__ hs, int n, int Hkv,
+                                                                         int splits, float* __restrict__ part) {
+  constexpr int TOK = 64, LD = D + 8, NB = D / 32, NBW = NB * NB / 4, CPR = D / 8;
+  static_assert(NBW >= 1, "at least one block per wave");
+  __shared__ __attribute__((aligned(16))) uint16_t a_s[TOK * LD];
+  __shared__ __attribute__((aligned(16))) uint16_t b_s[TOK * LD];
+  const int split = blockIdx.x, h = blockIdx.y;
+  const int per = (n + splits - 1) / splits;
+  const int t0 = split * per, t1 = min(n, t0 + per);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l32 = lane & 31, hf = lane >> 5, li = lane & 15, grp = lane >> 4;
+  f32x16 acc[NBW];
+#pragma unroll
+  for (int q = 0; q < NBW; ++q)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[q][r] = 0.f;
+  // transposing read of an operand fragment: lanes address row 4 hf + li / 4 (+ 8) of a 16-token slab, columns
+  // 16 (grp & 1) + 4 (li & 3) of a 32-column block; the result is lane (column l32, tokens 8 hf .. 8 hf + 7)
+  const int frag_off = (4 * hf + (li >> 2)) * LD + 16 * (grp & 1) + 4 * (li & 3);
+  auto frag = [&](const uint16_t* tile, int slab, int blk) __attribute__((always_inline)) -> bf16x8 {
+    const uint16_t* p = tile + frag_off + (16 * slab) * LD + 32 * blk;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((learn_lds_s16x4_ptr)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((learn_lds_s16x4_ptr)(p + 8 * LD));
+    return __builtin_shufflevector(__builtin_bit_cast(bf16x4, lo), __builtin_bit_cast(bf16x4, hi), 0, 1, 2, 3, 4, 5, 6, 7);
+  };
+  // the next 64 tokens travel through registers while the current ones are multiplied
+  constexpr int NLD = TOK * CPR / kLearnThreads;
+  static_assert(TOK * CPR % kLearnThreads == 0, "whole turns");
+  typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+  u32x4 ra[NLD], rb[NLD];
+  auto fetch = [&](int tb) __attribute__((always_inline)) {
+#pragma unroll
+    for (int k = 0; k < NLD; ++k) {
+      const int idx = threadIdx.x + k * kLearnThreads, tt = idx / CPR, c = idx % CPR, t = tb + tt;
+      ra[k] = u32x4{0, 0, 0, 0};
+      rb[k] = u32x4{0, 0, 0, 0};
+      if (t < t1) {
+        ra[k] = *reinterpret_cast<const u32x4*>(hn + ((size_t)t * Hkv + h) * D + 8 * c);
+        rb[k] = *reinterpret_cast<const u32x4*>(hs + ((size_t)t * Hkv + h) * D + 8 * c);
+      }
+    }
+  };
+  if (t0 < t1) fetch(t0);
+  for (int tb = t0; tb < t1; tb += TOK) {
+#pragma unroll
+    for (int k = 0; k < NLD; ++k) {
+      const int idx = threadIdx.x + k * kLearnThreads, tt = idx / CPR, c = idx % CPR;
+      *reinterpret_cast<u32x4*>(a_s + tt * LD + 8 * c) = ra[k];
+      *reinterpret_cast<u32x4*>(b_s + tt * LD + 8 * c) = rb[k];
+    }
+    __syncthreads();
+    if (tb + TOK < t1) fetch(tb + TOK);
+#pragma unroll
+    for (int slab = 0; slab < TOK / 16; ++slab) {
+#pragma unroll
+      for (int q = 0; q < NBW; ++q) {
+        const int blk = wave * NBW + q, ib = blk / NB, jb = blk % NB;
+        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(frag(a_s, slab, ib), frag(b_s, slab, jb), acc[q], 0, 0, 0);
+      }
+    }
+    __syncthreads();
+  }
+  // accumulator element r of lane (l32, hf): row 8 (r / 4) + 4 hf + r % 4 of the block, column l32
+#pragma unroll
+  for (int q = 0; q < NBW; ++q) {
+    const int blk = wave * NBW + q, ib = blk / NB, jb = blk % NB;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int i = 32 * ib + 8 * (r >> 2) + 4 * hf + (r & 3), j = 32 * jb + l32;
+      part[(((size_t)split * Hkv + h) * D + i) * D + j] = acc[q][r];
+    }
+  }
 }
 
 // grid (Hkv); dynamic LDS: D columns of D + 1 floats, then D floats (sigma), then D ints (rank).
@@ -251,8 +335,12 @@ template <typename T, int D>
 hipError_t launch_learn_td(const void* hn, const void* hs, int n, int Hkv, float gamma, float* U_out, float* sigma_out,
                            int* k_out, void* U_packed, int r_pad, float* part, hipStream_t s) {
   const int splits = learn_token_splits(n);
-  hipLaunchKernelGGL((cov_partial_kernel<T, D>), dim3(D / 16, Hkv, splits), dim3(kLearnThreads), 0, s,
-                     static_cast<const T*>(hn), static_cast<const T*>(hs), n, Hkv, splits, part);
+  if constexpr (sizeof(T) == 2)
+    hipLaunchKernelGGL((cov_partial_mfma_kernel<D>), dim3(splits, Hkv), dim3(kLearnThreads), 0, s,
+                       static_cast<const uint16_t*>(hn), static_cast<const uint16_t*>(hs), n, Hkv, splits, part);
+  else
+    hipLaunchKernelGGL((cov_partial_kernel<T, D>), dim3(D / 16, Hkv, splits), dim3(kLearnThreads), 0, s,
+                       static_cast<const T*>(hn), static_cast<const T*>(hs), n, Hkv, splits, part);
   const size_t smem = ((size_t)D * (D + 1) + 2 * D) * sizeof(float);
   auto kernel = jacobi_svd_kernel<T, D>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);

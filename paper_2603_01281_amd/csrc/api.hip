@@ -262,7 +262,7 @@ seka_status seka_edit_keys_packed(const void* K_in, void* K_out, const seka_shap
 
 size_t seka_decode_workspace_bytes(const seka_shape* sh) {
   if (check_shape(sh, true) != SEKA_OK) return 0;
-  return seka::decode_workspace_bytes(sh->B, sh->S, sh->Hq, sh->Hkv, sh->D);
+  return seka::decode_workspace_bytes(sh->B, sh->S, sh->Hq, sh->Hkv, sh->D, sh->dtype);
 }
 
 namespace {
@@ -280,7 +280,7 @@ seka_status check_decode(const void* q, const void* K, const void* V, void* O, f
   const size_t nq = (size_t)sh->B * sh->Hq * sh->D * es;
   const size_t nk = (size_t)sh->B * sh->S * sh->Hkv * sh->D * es;
   if (ranges_overlap(O, nq, q, nq) || ranges_overlap(O, nq, K, nk) || ranges_overlap(O, nq, V, nk)) return SEKA_ERR_ALIAS;
-  *need = seka::decode_workspace_bytes(sh->B, sh->S, sh->Hq, sh->Hkv, sh->D);
+  *need = seka::decode_workspace_bytes(sh->B, sh->S, sh->Hq, sh->Hkv, sh->D, sh->dtype);
   return SEKA_OK;
 }
 }  // namespace

@@ -54,7 +54,7 @@ hipError_t launch_route(const void* Q, int B, int S, int Hq, int Hkv, int D, int
                         hipStream_t s, const int* lens = nullptr, const int* cu = nullptr, int total = 0,
                         int window = 0);
 
-size_t decode_workspace_bytes(int B, int S, int Hq, int Hkv, int D);
+size_t decode_workspace_bytes(int B, int S, int Hq, int Hkv, int D, int dtype);
 constexpr size_t kDecodeStaticScratchBytes = (size_t)SEKA_DECODE_STATIC_MAX_BYTES;   // the library-owned buffer
 // Device address of the library-owned partial-state buffer on the current device (resolved once per device).
 hipError_t decode_static_scratch(void** out);

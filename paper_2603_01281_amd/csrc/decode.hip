@@ -6,10 +6,11 @@
 // HBM-bound: every cached key and value is read once (2 * B * S * Hkv * D elements), a few flops per byte.
 // Stage 1: grid (splits, KV head x head chunk, prompt); a workgroup streams its range of cached tokens with
 // 16-byte loads (a row is 16 consecutive lanes for bf16 at D = 128, so one wave instruction fetches whole
-// rows), scores them against the GP query heads of its KV head that it keeps in registers (the GQA group
-// shares every byte read), and keeps one online-softmax state per head and lane group with a lazily raised
-// reference exponent.  Partial states are merged across lanes, waves (LDS) and splits (stage 2, fixed order, so
-// the result does not depend on scheduling).
+// rows) and scores them against all the query heads of its KV head (the GQA group shares every byte read),
+// keeping one online-softmax state per head with a lazily raised reference exponent: on the matrix cores for
+// bf16 caches (decode_partial_mfma_kernel), on the vector unit for fp32 ones (decode_partial_kernel).  Partial
+// states are merged across lanes, waves (LDS) and splits (stage 2, fixed order, so the result does not depend on
+// scheduling).
 #include <mutex>
 
 #include "common.h"
@@ -38,8 +39,8 @@ __host__ __device__ inline int decode_heads_per_group(int G) {
 }
 
 // Splits of the cached range per (prompt, head group): about kDecTargetWG workgroups in all, at least kDecMinRows tokens each.
-__host__ __device__ inline int decode_splits(int B, int Hkv, int G, int S) {
-  const int groups = B * Hkv * (G / decode_heads_per_group(G));
+__host__ __device__ inline int decode_splits(int B, int Hkv, int G, int S, int heads_per_wg) {
+  const int groups = B * Hkv * (G / heads_per_wg);
   int want = (kDecTargetWG + groups - 1) / groups;
   const int cap = S / kDecMinRows > 1 ? S / kDecMinRows : 1;
   if (want > cap) want = cap;
@@ -49,16 +50,6 @@ __host__ __device__ inline int decode_splits(int B, int Hkv, int G, int S) {
 
 template <typename T> struct DecElem;
 template <> struct DecElem<uint16_t> {
-  static constexpr int EPL = 8;         // elements per 16-byte load
-  __device__ static void load(const uint16_t* p, float (&out)[8]) {
-    const uint4 v = *reinterpret_cast<const uint4*>(p);
-    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      out[2 * i] = __uint_as_float(w[i] << 16);
-      out[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-    }
-  }
   __device__ static void store(uint16_t* p, float v) {
     const __bf16 b = (__bf16)v;
     *p = __builtin_bit_cast(uint16_t, b);
@@ -102,6 +93,7 @@ __device__ __forceinline__ void merge_state(float& m, float& l, float (&o)[N], f
 }
 
 // partial state of one (prompt, query head, split): D unnormalised outputs, then m (base-2 exponent), then l
+// (fp32 caches: every product on the vector unit, exactness over speed)
 template <typename T, int D, int GP>
 __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(const T* __restrict__ q, const T* __restrict__ K,
                                                                      const T* __restrict__ V, const int* __restrict__ lens,
@@ -142,80 +134,10 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(const T* __
   const T* Kb = K + ((size_t)b * S * Hkv + h) * D + c * EPL;
   const T* Vb = V + ((size_t)b * S * Hkv + h) * D + c * EPL;
   const int step = kDecWaves * KPW;                      // rows per workgroup turn
-  constexpr bool PACKED = sizeof(T) == 2;      // bf16: both products on the packed dot-product instruction
-  uint32_t qw[GP][4];                          // PACKED: the query chunk as it is stored (pairs of bf16)
-  if (PACKED) {
-#pragma unroll
-    for (int g = 0; g < GP; ++g) {
-      const uint4 t4 = *reinterpret_cast<const uint4*>(q + ((size_t)b * Hq + hq0 + g) * D + c * EPL);
-      qw[g][0] = t4.x; qw[g][1] = t4.y; qw[g][2] = t4.z; qw[g][3] = t4.w;
-    }
-  }
   for (int turn = k0; turn < k1; turn += UNR * step) {      // workgroup-uniform trip count
     const int base = turn + wave * KPW + kk;
     bool ok[UNR];
-    float sc[UNR][GP];
-    if (PACKED) {
-      uint4 kr[UNR], vr[UNR];
-#pragma unroll
-      for (int u = 0; u < UNR; ++u) {
-        const int row = base + u * step;
-        ok[u] = row < k1;
-        const size_t r = (size_t)(ok[u] ? row : k1 - 1) * rowstride;      // clamped: loads stay inside the cache
-        kr[u] = *reinterpret_cast<const uint4*>(Kb + r);
-        vr[u] = *reinterpret_cast<const uint4*>(Vb + r);
-      }
-#pragma unroll
-      for (int u = 0; u < UNR; ++u) {
-#pragma unroll
-        for (int g = 0; g < GP; ++g) {
-          float t = dec_dot2(qw[g][0], kr[u].x, 0.f);
-          t = dec_dot2(qw[g][1], kr[u].y, t);
-          t = dec_dot2(qw[g][2], kr[u].z, t);
-          t = dec_dot2(qw[g][3], kr[u].w, t);
-          t = row_sum<LPR>(t) * c2;
-          sc[u][g] = ok[u] ? t : -INFINITY;
-        }
-      }
-      // one reference check per head and turn; probabilities are rounded to bf16 and that rounded value feeds both
-      // the row sum and the PV product (two cached rows per packed instruction)
-      uint32_t pp[UNR / 2][GP];
-#pragma unroll
-      for (int g = 0; g < GP; ++g) {
-        float smax = sc[0][g];
-#pragma unroll
-        for (int u = 1; u < UNR; ++u) smax = fmaxf(smax, sc[u][g]);
-        if (smax > m[g] + kDecSlack) {                     // rare after the first rows
-          const float alpha = __builtin_amdgcn_exp2f(m[g] - smax);
-          m[g] = smax;
-          l[g] *= alpha;
-#pragma unroll
-          for (int e = 0; e < EPL; ++e) o[g][e] *= alpha;
-        }
-#pragma unroll
-        for (int pr = 0; pr < UNR / 2; ++pr) {
-          const bf16x2 p2 = {(__bf16)__builtin_amdgcn_exp2f(sc[2 * pr][g] - m[g]),
-                             (__bf16)__builtin_amdgcn_exp2f(sc[2 * pr + 1][g] - m[g])};
-          pp[pr][g] = __builtin_bit_cast(uint32_t, p2);
-          l[g] = dec_dot2(pp[pr][g], 0x3f803f80u, l[g]);
-        }
-      }
-#pragma unroll
-      for (int pr = 0; pr < UNR / 2; ++pr) {
-        const uint32_t va[4] = {vr[2 * pr].x, vr[2 * pr].y, vr[2 * pr].z, vr[2 * pr].w};
-        const uint32_t vb[4] = {vr[2 * pr + 1].x, vr[2 * pr + 1].y, vr[2 * pr + 1].z, vr[2 * pr + 1].w};
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          const uint32_t lo = __builtin_amdgcn_perm(vb[w], va[w], 0x05040100u);   // (row a, row b) of element 2 w
-          const uint32_t hi = __builtin_amdgcn_perm(vb[w], va[w], 0x07060302u);   // ... of element 2 w + 1
-#pragma unroll
-          for (int g = 0; g < GP; ++g) {
-            o[g][2 * w] = dec_dot2(lo, pp[pr][g], o[g][2 * w]);
-            o[g][2 * w + 1] = dec_dot2(hi, pp[pr][g], o[g][2 * w + 1]);
-          }
-        }
-      }
-    } else {
+    {
       float kf[UNR][EPL], vf[UNR][EPL];
 #pragma unroll
       for (int u = 0; u < UNR; ++u) {
@@ -282,6 +204,204 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(const T* __
       const float aw = __builtin_amdgcn_exp2f(sm_ml[w][g][0] - mm);
       ll += sm_ml[w][g][1] * aw;
       oo += sm_o[w][g][d] * aw;
+    }
+    float* dst = part + (((size_t)b * Hq + hq0 + g) * splits + split) * (D + 2);
+    dst[d] = oo;
+    if (d == 0) {
+      dst[D] = mm;
+      dst[D + 1] = ll;
+    }
+  }
+}
+
+// Stage 1 for bf16 caches on the matrix cores.  Same grid, split ranges and partial-state layout as the kernel
+// above; what changes is who does the arithmetic.  The query heads of the group (HP <= 16 of them, padded to the 32
+// columns of the instruction) take the place that a tile of queries has in the prefill kernel:
+//   S^T (32 keys x heads)   = K (32 keys x D) q^T        D/16 x v_mfma_f32_32x32x16_bf16
+//   O^T (D x heads)        += V^T (D x 32 keys) P^T      2 D/32 of them
+// Keys and values are loaded as whole rows (every cache line requested once; fragments fetched straight from
+// global memory, 32 bytes per lane pair, cost twice the time) and pass through a wave-private LDS tile with padded
+// rows: K comes back with 16-byte reads, then V takes the tile over and comes back through transposing reads,
+// so that the vector unit is left with the softmax alone (one fma, one exponential and half a conversion per key
+// and lane) instead of every product, and a wave's next 32 keys and values (16 KB) are in flight while it works
+// on the current ones.  Waves take the 32-key blocks of the workgroup's range in turn and never synchronise
+// before the final merge.  Probabilities are rounded to bf16 once; that value feeds the row sum and the product.
+typedef __attribute__((address_space(3))) s16x4* dec_lds_s16x4_ptr;
+constexpr int kDecMfmaMaxHeads = 16;
+
+__host__ __device__ inline int decode_heads_per_group_mfma(int G) {
+  if (G <= kDecMfmaMaxHeads) return G;
+  for (int hp = kDecMfmaMaxHeads; hp > 1; --hp)
+    if (G % hp == 0) return hp;
+  return 1;
+}
+
+template <int D>
+__global__ __launch_bounds__(kDecThreads, 2) void decode_partial_mfma_kernel(const uint16_t* __restrict__ q,
+                                                                          const uint16_t* __restrict__ K,
+                                                                          const uint16_t* __restrict__ V,
+                                                                          const int* __restrict__ lens, int S, int Hq,
+                                                                          int Hkv, int HP, float c2, int splits,
+                                                                          float* __restrict__ part) {
+  constexpr int BK = 32;                   // keys per block
+  constexpr int LD = D + 8;                // LDS row stride of the V tile (elements): transposing reads conflict-free
+  constexpr int OLD = D + 4;               // row stride of the merge area (floats)
+  constexpr int KS = D / 16, NB = D / 32;
+  constexpr int CPR = D / 8, RPI = 64 / CPR, NV = BK / RPI;   // V rows: 16-byte chunks per row, rows per load, loads
+  constexpr int kTileBytes = BK * LD * 2;
+  constexpr int kMergeBytes = kDecMfmaMaxHeads * OLD * 4;
+  __shared__ __attribute__((aligned(16))) unsigned char smem[kDecWaves * (kTileBytes > kMergeBytes ? kTileBytes : kMergeBytes)];
+  __shared__ float sm_ml[kDecWaves][kDecMfmaMaxHeads][2];
+
+  const int G = Hq / Hkv;
+  const int chunks = G / HP;
+  const int b = blockIdx.z, h = blockIdx.y / chunks, hq0 = h * G + (blockIdx.y % chunks) * HP;
+  const int split = blockIdx.x;
+  const int n = lens ? min(max(lens[b], 0), S) : S;
+  const int per = (S + splits - 1) / splits;
+  const int k0 = split * per, k1 = min(n, k0 + per);
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int l32 = lane & 31, hf = lane >> 5, li = lane & 15, grp = lane >> 4;
+  uint16_t* vt = reinterpret_cast<uint16_t*>(smem + (size_t)wave * kTileBytes);
+
+  typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // (a plain vector type: arrays of it stay in registers)
+  // B operand of the score product: lane (head l32, hf) holds q[head][16 s + 8 hf ..][0..7]; padding heads are zero
+  bf16x8 qf[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    u32x4 t = {0, 0, 0, 0};
+    if (l32 < HP) t = *reinterpret_cast<const u32x4*>(q + ((size_t)b * Hq + hq0 + l32) * D + 16 * s + 8 * hf);
+    qf[s] = __builtin_bit_cast(bf16x8, t);
+  }
+
+  const size_t rowstride = (size_t)Hkv * D;
+  const uint16_t* Kb = K + ((size_t)b * S * Hkv + h) * D;
+  const uint16_t* Vb = V + ((size_t)b * S * Hkv + h) * D;
+  // both tiles arrive as whole rows (a row is CPR consecutive lanes: every cache line is requested once)
+  u32x4 kr[NV], vr[NV];
+  auto fetch = [&](int kb) __attribute__((always_inline)) {       // rows clamped into the range: loads stay inside the cache
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const size_t rv = (size_t)min(kb + RPI * i + lane / CPR, k1 - 1) * rowstride + 8 * (lane % CPR);
+      kr[i] = *reinterpret_cast<const u32x4*>(Kb + rv);
+      vr[i] = *reinterpret_cast<const u32x4*>(Vb + rv);
+    }
+  };
+  // transposing read of a V^T fragment (32 values of d x 16 keys): lanes address key 4 hf + li / 4 (+ 8) of the
+  // 16-key slab, columns 16 (grp & 1) + 4 (li & 3) of the 32-column block; lane (d l32, hf) receives the keys in
+  // the order in which the score accumulator holds them (element e: key 8 (e / 4) + 4 hf + e % 4)
+  const int frag_off = (4 * hf + (li >> 2)) * LD + 16 * (grp & 1) + 4 * (li & 3);
+  auto vfrag = [&](int slab, int blk) __attribute__((always_inline)) -> bf16x8 {
+    const uint16_t* p = vt + frag_off + (16 * slab) * LD + 32 * blk;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((dec_lds_s16x4_ptr)(p));
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((dec_lds_s16x4_ptr)(p + 8 * LD));
+    return __builtin_shufflevector(__builtin_bit_cast(bf16x4, lo), __builtin_bit_cast(bf16x4, hi), 0, 1, 2, 3, 4, 5, 6, 7);
+  };
+
+  // state of head l32 (both halves hf keep the same m; l is this lane's share of the row sum)
+  float m = kNegBig, l = 0.f;
+  f32x16 oacc[NB];
+#pragma unroll
+  for (int i = 0; i < NB; ++i)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[i][r] = 0.f;
+
+  int kb = k0 + wave * BK;
+  if (kb < k1) fetch(kb);
+  for (; kb < k1; kb += kDecWaves * BK) {
+    // K rows to the wave's tile, back as A fragments (lane (key l32, hf): 16 bytes at d = 16 s + 8 hf); then the V
+    // rows take the tile over.  A wave's LDS operations execute in program order; the fences are for the compiler.
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+      *reinterpret_cast<u32x4*>(vt + (RPI * i + lane / CPR) * LD + 8 * (lane % CPR)) = kr[i];
+    asm volatile("" ::: "memory");
+    f32x16 sacc;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(vt + l32 * LD + 16 * s + 8 * hf);
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc, 0, 0, 0);
+    }
+    asm volatile("" ::: "memory");
+#pragma unroll
+    for (int i = 0; i < NV; ++i)
+      *reinterpret_cast<u32x4*>(vt + (RPI * i + lane / CPR) * LD + 8 * (lane % CPR)) = vr[i];
+    asm volatile("" ::: "memory");
+    const int kb_next = kb + kDecWaves * BK;
+    const bool full = kb + BK <= k1;
+    if (kb_next < k1) fetch(kb_next);      // the registers are free again: next block's loads fly during the softmax
+
+    float t[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t[r] = sacc[r] * c2;
+    if (!full) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        if (kb + 16 * (r >> 3) + 8 * ((r >> 2) & 1) + 4 * hf + (r & 3) >= k1) t[r] = -INFINITY;
+    }
+    float bmax = t[0];
+#pragma unroll
+    for (int r = 1; r < 16; ++r) bmax = fmaxf(bmax, t[r]);
+    bmax = fmaxf(bmax, __shfl_xor(bmax, 32));
+    const bool raise = bmax > m + kDecSlack;
+    if (__any(raise)) {                    // rare after the first blocks
+      const float alpha = raise ? __builtin_amdgcn_exp2f(m - bmax) : 1.f;
+      if (raise) m = bmax;
+      l *= alpha;
+#pragma unroll
+      for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) oacc[i][r] *= alpha;
+    }
+    bf16x8 pb[2];
+#pragma unroll
+    for (int sl = 0; sl < 2; ++sl) {
+#pragma unroll
+      for (int e = 0; e < 8; e += 2) {
+        const bf16x2 p2 = {(__bf16)__builtin_amdgcn_exp2f(t[8 * sl + e] - m), (__bf16)__builtin_amdgcn_exp2f(t[8 * sl + e + 1] - m)};
+        pb[sl][e] = p2[0];
+        pb[sl][e + 1] = p2[1];
+        l = dec_dot2(__builtin_bit_cast(uint32_t, p2), 0x3f803f80u, l);
+      }
+    }
+#pragma unroll
+    for (int sl = 0; sl < 2; ++sl)
+#pragma unroll
+      for (int i = 0; i < NB; ++i) oacc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vfrag(sl, i), pb[sl], oacc[i], 0, 0, 0);
+    asm volatile("" ::: "memory");         // the tile is rewritten only after these reads
+  }
+
+  // ---- merge the waves: lane (head l32, hf) holds O[head][32 i + 8 (r / 4) + 4 hf + r % 4] ----
+  l += __shfl_xor(l, 32);
+  __syncthreads();                         // every wave is done with its V tile: the area becomes the merge area
+  float* sm_o = reinterpret_cast<float*>(smem) + (size_t)wave * kDecMfmaMaxHeads * OLD;
+  if (l32 < HP) {
+#pragma unroll
+    for (int i = 0; i < NB; ++i)
+#pragma unroll
+      for (int r4 = 0; r4 < 4; ++r4)
+        *reinterpret_cast<f32x4*>(sm_o + l32 * OLD + 32 * i + 8 * r4 + 4 * hf) =
+            f32x4{oacc[i][4 * r4], oacc[i][4 * r4 + 1], oacc[i][4 * r4 + 2], oacc[i][4 * r4 + 3]};
+    if (hf == 0) {
+      sm_ml[wave][l32][0] = m;
+      sm_ml[wave][l32][1] = l;
+    }
+  }
+  __syncthreads();
+  const float* sm_all = reinterpret_cast<const float*>(smem);
+  for (int idx = threadIdx.x; idx < HP * D; idx += kDecThreads) {
+    const int g = idx / D, d = idx % D;
+    float mm = sm_ml[0][g][0];
+#pragma unroll
+    for (int w = 1; w < kDecWaves; ++w) mm = fmaxf(mm, sm_ml[w][g][0]);
+    float ll = 0.f, oo = 0.f;
+#pragma unroll
+    for (int w = 0; w < kDecWaves; ++w) {
+      const float aw = __builtin_amdgcn_exp2f(sm_ml[w][g][0] - mm);
+      ll += sm_ml[w][g][1] * aw;
+      oo += sm_all[((size_t)w * kDecMfmaMaxHeads + g) * OLD + d] * aw;
     }
     float* dst = part + (((size_t)b * Hq + hq0 + g) * splits + split) * (D + 2);
     dst[d] = oo;
@@ -395,17 +515,34 @@ hipError_t decode_static_scratch(void** out) {
   return hipSuccess;
 }
 
-size_t decode_workspace_bytes(int B, int S, int Hq, int Hkv, int D) {
-  return (size_t)B * Hq * decode_splits(B, Hkv, Hq / Hkv, S) * (D + 2) * sizeof(float);
+// query heads that one stage-1 workgroup serves: the bf16 kernel takes up to 16 per KV head, the fp32 one up to 8
+static int decode_heads_per_wg(int G, int dtype) {
+  return dtype == SEKA_BF16 ? decode_heads_per_group_mfma(G) : decode_heads_per_group(G);
+}
+
+size_t decode_workspace_bytes(int B, int S, int Hq, int Hkv, int D, int dtype) {
+  const int G = Hq / Hkv;
+  return (size_t)B * Hq * decode_splits(B, Hkv, G, S, decode_heads_per_wg(G, dtype)) * (D + 2) * sizeof(float);
 }
 
 hipError_t launch_decode(const void* q, const void* K, const void* V, void* O, float* lse, const int* lens, int B, int S,
                          int Hq, int Hkv, int D, int dtype, float scale, void* workspace, hipStream_t s) {
-  const int splits = decode_splits(B, Hkv, Hq / Hkv, S);
+  const int G = Hq / Hkv, hp = decode_heads_per_wg(G, dtype);
+  const int splits = decode_splits(B, Hkv, G, S, hp);
   float* part = static_cast<float*>(workspace);
-  if (dtype == SEKA_BF16)
-    return D == 128 ? launch_decode_td<uint16_t, 128>(q, K, V, O, lse, lens, B, S, Hq, Hkv, scale, part, splits, s)
-                    : launch_decode_td<uint16_t, 64>(q, K, V, O, lse, lens, B, S, Hq, Hkv, scale, part, splits, s);
+  if (dtype == SEKA_BF16) {
+    const float c2 = scale * 1.4426950408889634f;
+    const dim3 grid(splits, Hkv * (G / hp), B);
+    const uint16_t *q16 = static_cast<const uint16_t*>(q), *K16 = static_cast<const uint16_t*>(K), *V16 = static_cast<const uint16_t*>(V);
+    if (D == 128) {
+      hipLaunchKernelGGL(decode_partial_mfma_kernel<128>, grid, dim3(kDecThreads), 0, s, q16, K16, V16, lens, S, Hq, Hkv, hp, c2, splits, part);
+      hipLaunchKernelGGL((decode_finish_kernel<uint16_t, 128>), dim3(Hq, B), dim3(kFinThreads), 0, s, part, Hq, splits, static_cast<uint16_t*>(O), lse);
+    } else {
+      hipLaunchKernelGGL(decode_partial_mfma_kernel<64>, grid, dim3(kDecThreads), 0, s, q16, K16, V16, lens, S, Hq, Hkv, hp, c2, splits, part);
+      hipLaunchKernelGGL((decode_finish_kernel<uint16_t, 64>), dim3(Hq, B), dim3(kFinThreads), 0, s, part, Hq, splits, static_cast<uint16_t*>(O), lse);
+    }
+    return hipGetLastError();
+  }
   return D == 128 ? launch_decode_td<float, 128>(q, K, V, O, lse, lens, B, S, Hq, Hkv, scale, part, splits, s)
                   : launch_decode_td<float, 64>(q, K, V, O, lse, lens, B, S, Hq, Hkv, scale, part, splits, s);
 }

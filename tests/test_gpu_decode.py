@@ -14,6 +14,9 @@ CASES = {
     "bf16_G7_splits": ("bf16", 1, 5000, 14, 2, 128, None),
     "bf16_G1_D64": ("bf16", 2, 300, 3, 3, 64, [299, 64]),
     "bf16_G16": ("bf16", 1, 400, 16, 1, 128, [333]),
+    "bf16_G32_two_head_chunks": ("bf16", 1, 1100, 32, 1, 128, [1061]),
+    "bf16_G20_two_head_chunks": ("bf16", 2, 700, 40, 2, 128, [700, 33]),
+    "bf16_G5_D64_splits": ("bf16", 2, 3000, 10, 2, 64, [3000, 1031]),
     "f32_G2": ("f32", 2, 257, 4, 2, 128, [257, 100]),
     "f32_D64_G3": ("f32", 1, 130, 6, 2, 64, None),
     "empty_prompt": ("bf16", 2, 128, 4, 2, 128, [0, 128]),

@@ -22,6 +22,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBPS = 8000.0         # MI355X HBM3E peak
 
 TRAFFIC_JSON = os.path.join(ROOT, "profiles", "attention_bf16_cfg3_hbm_traffic.json")
 
@@ -240,6 +241,75 @@ def time_stacked_edit(torch, seka, inputs, layers=16, iters=10):
             "algorithmic_bytes_out_of_place": 2 * nbytes + m.size, "algorithmic_bytes_in_place": int(2 * hl_bytes + m.size)}
 
 
+def read_probe(torch, B, S, Hkv):
+    """Time of a kernel that only reads a K/V cache of this shape (stand-alone probe built next to the library)."""
+    import subprocess
+    exe = os.path.join(ROOT, "hbm_read_probe.bin")
+    if not os.path.exists(exe):
+        return None
+    torch.cuda.synchronize()
+    r = subprocess.run([exe, str(B), str(S), str(Hkv)], capture_output=True, text=True, timeout=120)
+    if r.returncode != 0:
+        return {"error": r.stderr.strip()[-200:]}
+    return json.loads(r.stdout.strip().splitlines()[-1])
+
+
+def time_cold(torch, seka, inputs):
+    """The memory-bound entry points with nothing in a cache: every call works on its own set of buffers, the sets
+    rotated over more than 1.5 GB (six times the 256 MB last-level cache), per-call medians from events.  For each
+    benchmark shape and for one cache of 1 GB: the generation step (reads K and V once), the stand-alone key edit out
+    of place (reads K, writes K'), and as references for calls of that size a device copy of K (same bytes as the
+    edit) and a kernel that only reads K and V (same bytes as the generation step)."""
+    import numpy as np
+    shapes = {f"cfg{c}": dict(inputs.CONFIG_SHAPES[c]) for c in (2, 3, 4, 5)}
+    shapes["cache_1GB"] = dict(B=16, S=16384, Hq=32, Hkv=8, D=128, M=1, r=32)
+    recipes = {"cfg2": ("cover", 0.10, 0.10, 3), "cfg3": ("cover", 0.05, 0.20, 4), "cfg4": ("cover", 0.10, 0.10, 3),
+               "cfg5": ("lengths", 8, 64, 512), "cache_1GB": ("cover", 0.05, 0.20, 4)}
+    out = {}
+    for name, shp in shapes.items():
+        B, S, Hq, Hkv, D, M, r = (shp[k] for k in ("B", "S", "Hq", "Hkv", "D", "M", "r"))
+        gen = torch.Generator(device="cuda"); gen.manual_seed(77)
+        kv_bytes = B * S * Hkv * D * 2
+        nrot = max(2, int(1.6e9 // (2 * kv_bytes)) + 1)
+        mk = lambda *sh: torch.randn(sh, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        q = mk(B, Hq, D)
+        O = torch.empty_like(q)
+        Ks = [mk(B, S, Hkv, D) for _ in range(nrot)]
+        Vs = [mk(B, S, Hkv, D) for _ in range(nrot)]
+        U = torch.from_numpy(inputs.orthonormal_bases(Hkv, M, D, r, 0, "bf16").view(np.int16)).view(torch.bfloat16).cuda()
+        mask = torch.from_numpy(inputs.span_mask(B, S, 0, recipes[name])[0]).cuda()
+        w = torch.full((B, Hkv, M), 1.0 / M, device="cuda") if M > 1 else None
+        wsd = torch.empty(seka.seka_decode_workspace_bytes(B, S, Hq, Hkv, D, seka.SEKA_BF16), dtype=torch.uint8, device="cuda")
+
+        def median_us(fn):
+            for i in range(nrot):
+                fn(i)
+            torch.cuda.synchronize()
+            evs = []
+            for i in range(max(3 * nrot, 9)):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record(); fn(i % nrot); e1.record()
+                evs.append((e0, e1))
+            torch.cuda.synchronize()
+            return sorted(a.elapsed_time(b) for a, b in evs)[len(evs) // 2] * 1e3
+
+        dec = median_us(lambda i: seka.seka_attention_decode(q, Ks[i], Vs[i], O, workspace=wsd))
+        # the V buffers double as the edit's and the copy's outputs (same size, also rotated)
+        edit = median_us(lambda i: seka.seka_edit_keys(Ks[i], Vs[i], U, [1.0] * Hkv, mask, w=w))
+        copy = median_us(lambda i: Vs[i].copy_(Ks[i]))
+        row = {"kv_bytes": 2 * kv_bytes, "buffer_sets": nrot, "rank": M * r, "coverage": round(float(mask.float().mean()), 3),
+               "decode_us": round(dec, 1), "decode_GBps": round(2 * kv_bytes / dec / 1e3, 0),
+               "decode_frac_of_hbm_peak": round(2 * kv_bytes / dec / 1e3 / PEAK_HBM_GBPS, 3),
+               "edit_keys_us": round(edit, 1), "edit_keys_GBps": round(2 * kv_bytes / edit / 1e3, 0),
+               "edit_keys_frac_of_hbm_peak": round(2 * kv_bytes / edit / 1e3 / PEAK_HBM_GBPS, 3),
+               "device_copy_us": round(copy, 1), "device_copy_GBps": round(2 * kv_bytes / copy / 1e3, 0)}
+        del Ks, Vs
+        torch.cuda.empty_cache()
+        row["read_only_kernel"] = read_probe(torch, B, S, Hkv)
+        out[name] = row
+    return out
+
+
 def time_learn(torch, seka, inputs, n=16384, Hkv=8, D=128, iters=5):
     """Offline stage for one layer of configuration 3's shape: n paired sample tokens per KV head."""
     import numpy as np
@@ -383,6 +453,7 @@ def main():
     torch.cuda.empty_cache()
     if args.extras:
         out["edit_keys_16_layers"] = time_stacked_edit(torch, seka, inputs)      # 2.1 GB: after the stack is freed
+        out["cold_cache"] = time_cold(torch, seka, inputs)
         torch.cuda.empty_cache()
     try:
         out["mfma_only_rate"] = mfma_only_rate(torch)        # about a second; context for roofline.frac

@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libseka.so")
-PROBE = os.path.join(ROOT, "mfma_rate_probe.bin")
+PROBES = ["mfma_rate_probe", "hbm_read_probe"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 SOURCES = ["api.hip", "route.hip", "edit.hip", "decode.hip", "learn.hip", "attn_f32.hip", "attn_bf16.hip", "attn_bf16_d128.hip", "attn_bf16_d64.hip",
@@ -45,13 +45,16 @@ def build(verbose=False, extra=()):
         raise RuntimeError("link failed:\n" + r.stderr)
     if verbose:
         print("built", LIB)
-    # stand-alone probe of the device's sustained MFMA-only rate (lives beside bench.py, which runs it)
-    cmd = [HIPCC, *[f for f in FLAGS if f != "-fPIC"], os.path.join(ROOT, "mfma_rate_probe.hip"), "-o", PROBE]
-    r = subprocess.run(cmd, capture_output=True, text=True)
-    if r.returncode != 0:
-        raise RuntimeError("probe build failed:\n" + r.stderr)
-    if verbose:
-        print("built", PROBE)
+    # stand-alone probes (they live beside bench.py, which runs them): the device's sustained MFMA-only rate, and
+    # the time of a kernel that only reads a key/value cache of a given shape
+    for probe in PROBES:
+        exe = os.path.join(ROOT, probe + ".bin")
+        cmd = [HIPCC, *[f for f in FLAGS if f != "-fPIC"], os.path.join(ROOT, probe + ".hip"), "-o", exe]
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"build of {probe} failed:\n" + r.stderr)
+        if verbose:
+            print("built", exe)
     return LIB
 
 

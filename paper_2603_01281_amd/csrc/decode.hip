@@ -221,7 +221,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(const T* __
 //   O^T (D x heads)        += V^T (D x 32 keys) P^T      2 D/32 of them
 // Keys and values are loaded as whole rows (every cache line requested once; fragments fetched straight from
 // global memory, 32 bytes per lane pair, cost twice the time) and pass through a wave-private LDS tile with padded
-// rows: K comes back with 16-byte reads, then V takes the tile over and comes back through transposing reads,
+// rows (no bank conflicts): K comes back with 16-byte reads, then V takes the tile over and comes back through transposing reads,
 // so that the vector unit is left with the softmax alone (one fma, one exponential and half a conversion per key
 // and lane) instead of every product, and a wave's next 32 keys and values (16 KB) are in flight while it works
 // on the current ones.  Waves take the 32-key blocks of the workgroup's range in turn and never synchronise
@@ -244,7 +244,10 @@ __global__ __launch_bounds__(kDecThreads, 2) void decode_partial_mfma_kernel(con
                                                                           int Hkv, int HP, float c2, int splits,
                                                                           float* __restrict__ part) {
   constexpr int BK = 32;                   // keys per block
-  constexpr int LD = D + 8;                // LDS row stride of the V tile (elements): transposing reads conflict-free
+  // LDS row strides (elements).  K rows are read back 16 bytes per lane by 16 consecutive rows: a stride of 16 bytes
+  // mod 256 spreads them over all banks.  V rows come back through transposing reads, where 16 lanes take 32 bytes
+  // of each of four consecutive rows: a stride of 64 bytes mod 256 keeps those apart.
+  constexpr int LDK = D + 8, LD = D + 32;
   constexpr int OLD = D + 4;               // row stride of the merge area (floats)
   constexpr int KS = D / 16, NB = D / 32;
   constexpr int CPR = D / 8, RPI = 64 / CPR, NV = BK / RPI;   // V rows: 16-byte chunks per row, rows per load, loads
@@ -314,14 +317,14 @@ __global__ __launch_bounds__(kDecThreads, 2) void decode_partial_mfma_kernel(con
     // rows take the tile over.  A wave's LDS operations execute in program order; the fences are for the compiler.
 #pragma unroll
     for (int i = 0; i < NV; ++i)
-      *reinterpret_cast<u32x4*>(vt + (RPI * i + lane / CPR) * LD + 8 * (lane % CPR)) = kr[i];
+      *reinterpret_cast<u32x4*>(vt + (RPI * i + lane / CPR) * LDK + 8 * (lane % CPR)) = kr[i];
     asm volatile("" ::: "memory");
     f32x16 sacc;
 #pragma unroll
     for (int r = 0; r < 16; ++r) sacc[r] = 0.f;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(vt + l32 * LD + 16 * s + 8 * hf);
+      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(vt + l32 * LDK + 16 * s + 8 * hf);
       sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc, 0, 0, 0);
     }
     asm volatile("" ::: "memory");

@@ -10,8 +10,7 @@
 // lanes that hold the matching key elements (the row order of U fed to the second GEMM is
 // permuted to make that so).  Tiles without highlighted tokens are a plain 16-byte copy (or are
 // skipped entirely when editing in place).  U is staged in LDS only by workgroups that need it; at large
-// ranks (a 70 KB staging area, two workgroups per CU) a workgroup takes several tiles in turn, stages once and
-// keeps the next tile's keys in flight while it works on the current one.
+// ranks (a 70 KB staging area, two workgroups per CU) a tile is 128 tokens and a wave owns two groups of 16.
 #include "common.h"
 
 namespace seka {
@@ -40,12 +39,13 @@ __device__ __forceinline__ void edit_prompt_extent(const int* __restrict__ cu, i
   }
 }
 
-template <int D>
+template <int D, int TG>
 __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint16_t* __restrict__ K_in,
                                                                       uint16_t* __restrict__ K_out, int S, int Hkv,
                                                                       SteerArgs st, int inplace, int Rpad,
-                                                                      const int* __restrict__ cu, int total, int tpw) {
+                                                                      const int* __restrict__ cu, int total) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  constexpr int TOK = kEditTokens * TG;        // tokens per tile: a wave owns TG groups of 16 consecutive tokens
   constexpr int UT_LD = D + 8;                 // row stride of U^T [Rpad][D] in elements
   const int UN_LD = Rpad + 8;                  // row stride of U (column-permuted) [D][Rpad]
   uint16_t* UT = reinterpret_cast<uint16_t*>(smem);
@@ -60,58 +60,67 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint
   edit_prompt_extent(cu, total, b, S, tok0, len);
   const float gain = st.gain[h];
   const float kscale = st.kscale[h];
-  // A workgroup takes `tpw` consecutive 64-token tiles (one for small ranks; several for large ones, whose
-  // operand staging is expensive and whose LDS footprint leaves few workgroups per CU): U is staged at the first
-  // tile that needs it, and the next tile's keys are requested before the current one is worked on.
-  const int tile_first = blockIdx.x * tpw;
-  if (tile_first * kEditTokens >= len) return;           // workgroup-uniform, before any barrier
-  const int ntile = min(tpw, (len - tile_first * kEditTokens + kEditTokens - 1) / kEditTokens);
+  // One tile per workgroup.  At large ranks (a 70 KB staging area: two workgroups per CU) a wave owns two token
+  // groups (TG = 2): twice the bytes in flight per wave, and every U fragment read from LDS serves both groups.
+  const int tile = blockIdx.x;
+  if (tile * TOK >= len) return;                         // workgroup-uniform, before any barrier
   constexpr int KS = D / 32;
-  auto fetch = [&](int tile, int& mk_o, bool& valid_o, size_t& off_o, bf16x8 (&kr)[KS]) __attribute__((always_inline)) {
-    const int t = tile * kEditTokens + wave * 16 + j;
-    valid_o = t < len;
-    mk_o = valid_o ? st.mask[tok0 + t] : 0;
-    off_o = ((tok0 + (valid_o ? t : 0)) * Hkv + h) * D;
-    // in place, a wave whose 16 tokens are not highlighted neither edits nor copies: it does not read its keys
-    const bool need = valid_o && !(inplace && __ballot(mk_o != 0) == 0ull);
+  int mk[TG];
+  bool valid[TG];
+  size_t row_off[TG];
+  bf16x8 kreg[TG][KS];
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (need) v = *reinterpret_cast<const uint4*>(K_in + off_o + 32 * s + 8 * g);
-      kr[s] = __builtin_bit_cast(bf16x8, v);
-    }
+  for (int tg = 0; tg < TG; ++tg) {
+    const int t = tile * TOK + (wave * TG + tg) * 16 + j;
+    valid[tg] = t < len;
+    row_off[tg] = ((tok0 + (valid[tg] ? t : 0)) * Hkv + h) * D;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) kreg[tg][s] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+  }
+  auto load_keys = [&](int tg) __attribute__((always_inline)) {
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+      kreg[tg][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(K_in + row_off[tg] + 32 * s + 8 * g));
   };
-  int mk_n;
-  bool valid_n;
-  size_t off_n;
-  bf16x8 kn[KS];
-  fetch(tile_first, mk_n, valid_n, off_n, kn);
-  bool staged = false;                                   // workgroup-uniform
-  for (int ti = 0; ti < ntile; ++ti) {
-  const int mk = mk_n;
-  const bool valid = valid_n;
-  const size_t row_off = off_n;
-  bf16x8 kreg[KS];
+  // Out of place every key is needed whatever the mask says: the keys are requested first and the mask bytes
+  // travel with them.  In place a group whose 16 tokens are not highlighted is neither edited nor copied, so the
+  // mask decides which keys are read at all.
+  if (!inplace) {
 #pragma unroll
-  for (int s = 0; s < KS; ++s) kreg[s] = kn[s];
-  if (ti + 1 < ntile) fetch(tile_first + ti + 1, mk_n, valid_n, off_n, kn);
-  const bool wave_hl = __ballot(mk != 0) != 0ull;
-  const bool block_hl = __syncthreads_or(mk != 0) != 0;
+    for (int tg = 0; tg < TG; ++tg)
+      if (valid[tg]) load_keys(tg);
+  }
+#pragma unroll
+  for (int tg = 0; tg < TG; ++tg) mk[tg] = valid[tg] ? st.mask[tok0 + tile * TOK + (wave * TG + tg) * 16 + j] : 0;
+  if (inplace) {
+#pragma unroll
+    for (int tg = 0; tg < TG; ++tg)
+      if (valid[tg] && __ballot(mk[tg] != 0) != 0ull) load_keys(tg);
+  }
+  bool any_mk = false;
+#pragma unroll
+  for (int tg = 0; tg < TG; ++tg) any_mk = any_mk || mk[tg] != 0;
+  const bool wave_hl = __ballot(any_mk) != 0ull;
+  const bool block_hl = __syncthreads_or(any_mk) != 0;
   const bool steered = block_hl && gain != 0.f;
+  auto copy_out = [&]() __attribute__((always_inline)) {
+    if (inplace) return;
+#pragma unroll
+    for (int tg = 0; tg < TG; ++tg)
+      if (valid[tg]) {
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+          *reinterpret_cast<uint4*>(K_out + row_off[tg] + 32 * s + 8 * g) = __builtin_bit_cast(uint4, kreg[tg][s]);
+      }
+  };
 
   if (!steered) {
-    if (!inplace && valid) {
-#pragma unroll
-      for (int s = 0; s < KS; ++s)
-        *reinterpret_cast<uint4*>(K_out + row_off + 32 * s + 8 * g) = __builtin_bit_cast(uint4, kreg[s]);
-    }
-    continue;
+    copy_out();
+    return;
   }
 
   // ---- stage U (both orientations) and the per-column coefficients in LDS ----
   const int R = st.M * st.r;
-  if (!staged) {
-  staged = true;
   if (R != Rpad) {
     for (int i = threadIdx.x; i < (Rpad - R) * UT_LD; i += kEditThreads) UT[(size_t)R * UT_LD + i] = 0;
     for (int i = threadIdx.x; i < D * UN_LD; i += kEditThreads) UN[i] = 0;
@@ -150,71 +159,86 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint
     }
   }
   __syncthreads();
-  }
 
   if (!wave_hl) {
-    if (!inplace && valid) {
-#pragma unroll
-      for (int s = 0; s < KS; ++s)
-        *reinterpret_cast<uint4*>(K_out + row_off + 32 * s + 8 * g) = __builtin_bit_cast(uint4, kreg[s]);
-    }
-    continue;
+    copy_out();
+    return;
   }
 
   // ---- Z^T = U^T K^T, scaled by c_r and by the token's mask bit; packed as the next B operand ----
-  const float mbit = mk != 0 ? 1.f : 0.f;
+  // (a group without a highlighted token rides along: its mask bits are zero, its correction is exactly zero
+  // and its keys come out bit for bit as they went in)
+  float mbit[TG];
+#pragma unroll
+  for (int tg = 0; tg < TG; ++tg) mbit[tg] = mk[tg] != 0 ? 1.f : 0.f;
   constexpr int MAXKS2 = SEKA_MAX_RANK / 32;
-  bf16x8 zb[MAXKS2];
+  bf16x8 zb[TG][MAXKS2];
   const int nks2 = Rpad / 32;
 #pragma unroll
   for (int ks2 = 0; ks2 < MAXKS2; ++ks2) {
     if (ks2 < nks2) {
-      float zc[8];
+      float zc[TG][8];
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
         const int rb = 2 * ks2 + half;
-        f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+        f32x4 acc[TG];
+#pragma unroll
+        for (int tg = 0; tg < TG; ++tg) acc[tg] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
           const bf16x8 a = *reinterpret_cast<const bf16x8*>(UT + (size_t)(16 * rb + j) * UT_LD + 32 * s + 8 * g);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, kreg[s], acc, 0, 0, 0);
+#pragma unroll
+          for (int tg = 0; tg < TG; ++tg) acc[tg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, kreg[tg][s], acc[tg], 0, 0, 0);
         }
         const f32x4 c4 = *reinterpret_cast<const f32x4*>(cvec + 16 * rb + 4 * g);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) zc[4 * half + i] = acc[i] * c4[i] * mbit;
-      }
-      bf16x8 z;
+        for (int tg = 0; tg < TG; ++tg)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) z[e] = (__bf16)zc[e];
-      zb[ks2] = z;
+          for (int i = 0; i < 4; ++i) zc[tg][4 * half + i] = acc[tg][i] * c4[i] * mbit[tg];
+      }
+#pragma unroll
+      for (int tg = 0; tg < TG; ++tg) {
+        bf16x8 z;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) z[e] = (__bf16)zc[tg][e];
+        zb[tg][ks2] = z;
+      }
     }
   }
 
   // ---- C^T = U (c .* Z^T); rows of U are visited in the order that puts d = 32 s + 8 g + e in lane (j, g) ----
 #pragma unroll
   for (int s = 0; s < KS; ++s) {
-    float outv[8];
+    float outv[TG][8];
 #pragma unroll
     for (int half = 0; half < 2; ++half) {
       const int d_row = 32 * s + 8 * (j >> 2) + 4 * half + (j & 3);
-      f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+      f32x4 acc[TG];
+#pragma unroll
+      for (int tg = 0; tg < TG; ++tg) acc[tg] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
       for (int ks2 = 0; ks2 < MAXKS2; ++ks2) {
         if (ks2 < nks2) {
           const bf16x8 a = *reinterpret_cast<const bf16x8*>(UN + (size_t)d_row * UN_LD + 32 * ks2 + 8 * g);
-          acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, zb[ks2], acc, 0, 0, 0);
+#pragma unroll
+          for (int tg = 0; tg < TG; ++tg) acc[tg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, zb[tg][ks2], acc[tg], 0, 0, 0);
         }
       }
 #pragma unroll
-      for (int i = 0; i < 4; ++i) outv[4 * half + i] = (float)kreg[s][4 * half + i] * (1.f + mbit * (kscale - 1.f)) + acc[i];
-    }
-    bf16x8 o;
+      for (int tg = 0; tg < TG; ++tg)
 #pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = (__bf16)outv[e];
-    if (valid && (!inplace || mk != 0))
-      *reinterpret_cast<uint4*>(K_out + row_off + 32 * s + 8 * g) = __builtin_bit_cast(uint4, o);
+        for (int i = 0; i < 4; ++i)
+          outv[tg][4 * half + i] = (float)kreg[tg][s][4 * half + i] * (1.f + mbit[tg] * (kscale - 1.f)) + acc[tg][i];
+    }
+#pragma unroll
+    for (int tg = 0; tg < TG; ++tg) {
+      bf16x8 o;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = (__bf16)outv[tg][e];
+      if (valid[tg] && (!inplace || mk[tg] != 0))
+        *reinterpret_cast<uint4*>(K_out + row_off[tg] + 32 * s + 8 * g) = __builtin_bit_cast(uint4, o);
+    }
   }
-  }   // tiles of this workgroup
 }
 
 // fp32 path (small problems, exactness over speed): one workgroup = 16 tokens of one KV head.
@@ -289,20 +313,20 @@ hipError_t launch_edit_keys(const void* K_in, void* K_out, int B, int S, int Hkv
     const int R = steer.M * steer.r;
     const int Rpad = (R + 31) / 32 * 32;
     const size_t smem = ((size_t)Rpad * (D + 8) + (size_t)D * (Rpad + 8)) * 2 + (size_t)Rpad * 4;
-    const int tiles = (S + kEditTokens - 1) / kEditTokens;
-    // Tiles per workgroup (see the kernel): four at rank > 64 when that still leaves 1024 workgroups (measured at
-    // 8 prompts x 4096 tokens x 8 heads, rank 128: 37 us against 47 us with one; one is best everywhere else).
-    const int tpw = (Rpad > 64 && (long long)tiles * Hkv * B >= 4096) ? 4 : 1;
-    const dim3 grid((tiles + tpw - 1) / tpw, Hkv, B);
+    // Large ranks (a 70 KB staging area: two workgroups per CU): 128-token tiles, a wave owns two groups of 16 tokens.
+    const bool wide = Rpad > 64;
+    const int tok = wide ? 2 * kEditTokens : kEditTokens;
+    const dim3 grid((S + tok - 1) / tok, Hkv, B);
     auto launch = [&](auto kernel) -> hipError_t {
       hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                          hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
       if (e != hipSuccess) return e;
       hipLaunchKernelGGL(kernel, grid, dim3(kEditThreads), smem, s, static_cast<const uint16_t*>(K_in),
-                         static_cast<uint16_t*>(K_out), S, Hkv, steer, inplace, Rpad, cu, total, tpw);
+                         static_cast<uint16_t*>(K_out), S, Hkv, steer, inplace, Rpad, cu, total);
       return hipGetLastError();
     };
-    return D == 128 ? launch(edit_keys_bf16_kernel<128>) : launch(edit_keys_bf16_kernel<64>);
+    if (wide) return D == 128 ? launch(edit_keys_bf16_kernel<128, 2>) : launch(edit_keys_bf16_kernel<64, 2>);
+    return D == 128 ? launch(edit_keys_bf16_kernel<128, 1>) : launch(edit_keys_bf16_kernel<64, 1>);
   }
   const dim3 grid((S + 15) / 16, Hkv, B);
   if (D == 128)

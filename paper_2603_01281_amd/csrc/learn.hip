@@ -74,13 +74,14 @@ __global__ __launch_bounds__(kLearnThreads) void cov_partial_kernel(const T* __r
 // order of the additions) and the kernel becomes a single pass over both views: grid (splits, Hkv), a workgroup
 // stages 64 tokens x D of both views in LDS with 16-byte loads and every wave owns D*D/4096 blocks of 32 x 32 of
 // Omega.  Both MFMA operands run along the token axis, the strided one of the row-major [token][d] tiles, hence
-// the transposing LDS reads (rows padded by 16 bytes: no bank conflicts).
+// the transposing LDS reads (rows padded by 64 bytes: four consecutive rows, of which 16 lanes read 32 bytes each, fall
+// into different banks).
 typedef __attribute__((address_space(3))) s16x4* learn_lds_s16x4_ptr;
 template <int D>
 __global__ __launch_bounds__(kLearnThreads) void cov_partial_mfma_kernel(const uint16_t* __restrict__ hn,
                                                                          const uint16_t* __restrict__ hs, int n, int Hkv,
                                                                          int splits, float* __restrict__ part) {
-  constexpr int TOK = 64, LD = D + 8, NB = D / 32, NBW = NB * NB / 4, CPR = D / 8;
+  constexpr int TOK = 64, LD = D + 32, NB = D / 32, NBW = NB * NB / 4, CPR = D / 8;
   static_assert(NBW >= 1, "at least one block per wave");
   __shared__ __attribute__((aligned(16))) uint16_t a_s[TOK * LD];
   __shared__ __attribute__((aligned(16))) uint16_t b_s[TOK * LD];

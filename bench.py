@@ -216,6 +216,44 @@ def time_stress_masks(torch, seka, inputs):
     return out
 
 
+def time_query_side_bound(torch, seka, inputs):
+    """What applying the edit on the query side could save at best (paper Sec. 2, Eq. 5: q . (k + g P k) = (q + g P q) . k).
+    With Q' = Q + g P Q at hand, a key tile that lies fully inside a highlighted span needs no per-tile work; a tile
+    that a span only partly covers still needs the key-side edit (or both products and a per-key select).  The fused
+    kernel is timed on the configuration's mask and on the same mask with every fully covered 64-key tile cleared:
+    the second launch does exactly the per-tile work a query-side kernel would be left with, and nothing for Q' or
+    for switching between Q and Q', so its overhead is a lower bound on that kernel's.  (The second launch computes
+    a different function; it is a timing of the fused kernel on another mask, not a result.)"""
+    import numpy as np
+    out = {}
+    for name, cfg, recipe in (("cfg4", 4, ("cover", 0.10, 0.10, 3)), ("cfg2_70pct_contiguous", 2, None)):
+        shp = inputs.CONFIG_SHAPES[cfg]
+        B, S, Hq, Hkv, D, M, r = (shp[k] for k in ("B", "S", "Hq", "Hkv", "D", "M", "r"))
+        gen = torch.Generator(device="cuda"); gen.manual_seed(44 + cfg)
+        mk = lambda h: torch.randn((B, S, h, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        Q, K, V = mk(Hq), mk(Hkv), mk(Hkv)
+        O = torch.empty_like(Q)
+        U = torch.from_numpy(inputs.orthonormal_bases(Hkv, M, D, r, 0, "bf16").view(np.int16)).view(torch.bfloat16).cuda()
+        w = torch.full((B, Hkv, M), 1.0 / M, device="cuda") if M > 1 else None
+        if recipe is None:
+            m = np.zeros((B, S), np.uint8)
+            m[:, int(0.15 * S):int(0.85 * S)] = 1
+        else:
+            m = inputs.span_mask(B, S, 0, recipe)[0].astype(np.uint8)
+        tiles = m.reshape(B, S // 64, 64)
+        full = tiles.all(axis=2)
+        m2 = np.where(full[:, :, None], 0, tiles).reshape(B, S).astype(np.uint8)
+        fl = attn_flops(B, S, Hq, D)
+        res = {"tiles": int(tiles.shape[0] * tiles.shape[1]), "tiles_touched": int(tiles.any(axis=2).sum()), "tiles_fully_covered": int(full.sum())}
+        for key, mm in (("key_side_overhead_pct", m), ("query_side_lower_bound_overhead_pct", m2)):
+            mask = torch.from_numpy(mm).cuda()
+            plain, steer = paired_medians(torch, lambda: seka.seka_attention_plain(Q, K, V, O),
+                                          lambda: seka.seka_attention_prefill(Q, K, V, O, U, [1.0] * Hkv, mask, w=w), fl)
+            res[key] = round(100 * (steer / plain - 1), 2)
+        out[name] = res
+    return out
+
+
 def time_stacked_edit(torch, seka, inputs, layers=16, iters=10):
     """Steady-state bandwidth of the standalone key edit: the keys of 16 layers of configuration 3 in one launch
     (the layer index treated as extra batch: 64 x 8192 tokens x 8 KV heads x 128, 1.07 GB read and 1.07 GB written
@@ -445,6 +483,7 @@ def main():
         out["other_configs"] = {f"cfg{c}": time_config(torch, seka, inputs, c) for c in (2, 3, 4, 5)}
         out["offline_learn"] = time_learn(torch, seka, inputs)
         out["stress_masks_cfg2"] = time_stress_masks(torch, seka, inputs)
+        out["query_side_bound"] = time_query_side_bound(torch, seka, inputs)
     sample_item = None
     if steered_ix and not args.no_cpu_baseline:                 # keep (on the host) what the parity check needs
         it = layers[steered_ix[0]]

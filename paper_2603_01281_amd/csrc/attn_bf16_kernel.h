@@ -42,7 +42,7 @@ __device__ __forceinline__ bf16x8 lds_read_tr_pair(const uint16_t* p0, const uin
 }
 
 template <int D, int HPW, int RB, bool STEER, int VPAD>
-__global__ __launch_bounds__(64 * HPW * RB) void attention_bf16_kernel(AttnArgs a, SteerArgs st, int Rpad) {
+__global__ __launch_bounds__(64 * HPW * RB, D == 64 ? 4 : 1) void attention_bf16_kernel(AttnArgs a, SteerArgs st, int Rpad) {
   constexpr int NW = HPW * RB;
   constexpr int NT = 64 * NW;
   constexpr int BQ = 32 * RB;

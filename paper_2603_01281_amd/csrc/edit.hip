@@ -10,13 +10,14 @@
 // lanes that hold the matching key elements (the row order of U fed to the second GEMM is
 // permuted to make that so).  Tiles without highlighted tokens are a plain 16-byte copy (or are
 // skipped entirely when editing in place).  U is staged in LDS only by workgroups that need it; at large
-// ranks (a 70 KB staging area, two workgroups per CU) a tile is 128 tokens and a wave owns two groups of 16.
+// ranks a tile is 128 tokens, a wave owns two groups of 16, and U is staged once instead of twice.
 #include "common.h"
 
 namespace seka {
 
 namespace {
 
+typedef __attribute__((address_space(3))) s16x4* edit_lds_s16x4_ptr;
 constexpr int kEditThreads = 256;
 constexpr int kEditTokens = 64;   // tokens per workgroup (bf16 path)
 
@@ -46,10 +47,16 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint
                                                                       const int* __restrict__ cu, int total) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   constexpr int TOK = kEditTokens * TG;        // tokens per tile: a wave owns TG groups of 16 consecutive tokens
+  // Small ranks (TG = 1): U twice in LDS, each copy in the order one product reads it with 16-byte reads (U^T
+  // [Rpad][D], and U [D][Rpad] with permuted columns).  Large ranks (TG = 2, WIDE): U once, as stored ([D][Rpad],
+  // columns in order): the first product fetches its operand with transposing reads, the second with two 8-byte
+  // reads; half the LDS (35 KB instead of 70 KB at rank 128: four workgroups per CU instead of two) and a staging
+  // pass of plain 16-byte copies.
+  constexpr bool WIDE = TG == 2;
   constexpr int UT_LD = D + 8;                 // row stride of U^T [Rpad][D] in elements
-  const int UN_LD = Rpad + 8;                  // row stride of U (column-permuted) [D][Rpad]
+  const int UN_LD = Rpad + 8;                  // row stride of U [D][Rpad]
   uint16_t* UT = reinterpret_cast<uint16_t*>(smem);
-  uint16_t* UN = UT + (size_t)Rpad * UT_LD;
+  uint16_t* UN = WIDE ? UT : UT + (size_t)Rpad * UT_LD;
   float* cvec = reinterpret_cast<float*>(UN + (size_t)D * UN_LD);
 
   const int b = blockIdx.z, h = blockIdx.y;
@@ -60,8 +67,9 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint
   edit_prompt_extent(cu, total, b, S, tok0, len);
   const float gain = st.gain[h];
   const float kscale = st.kscale[h];
-  // One tile per workgroup.  At large ranks (a 70 KB staging area: two workgroups per CU) a wave owns two token
-  // groups (TG = 2): twice the bytes in flight per wave, and every U fragment read from LDS serves both groups.
+  // One tile per workgroup.  At large ranks (35 KB of LDS: four workgroups per CU where small ranks have eight) a
+  // wave owns two token groups (TG = 2): twice the bytes in flight per wave, and every U fragment read from LDS
+  // serves both groups.
   const int tile = blockIdx.x;
   if (tile * TOK >= len) return;                         // workgroup-uniform, before any barrier
   constexpr int KS = D / 32;
@@ -119,14 +127,30 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint
     return;
   }
 
-  // ---- stage U (both orientations) and the per-column coefficients in LDS ----
+  // ---- stage U and the per-column coefficients in LDS ----
   const int R = st.M * st.r;
   if (R != Rpad) {
-    for (int i = threadIdx.x; i < (Rpad - R) * UT_LD; i += kEditThreads) UT[(size_t)R * UT_LD + i] = 0;
+    if (!WIDE)
+      for (int i = threadIdx.x; i < (Rpad - R) * UT_LD; i += kEditThreads) UT[(size_t)R * UT_LD + i] = 0;
     for (int i = threadIdx.x; i < D * UN_LD; i += kEditThreads) UN[i] = 0;
     __syncthreads();
   }
-  {
+  if (WIDE) {
+    const uint16_t* Uh = reinterpret_cast<const uint16_t*>(st.U) + (size_t)h * st.M * D * st.r;
+    const int r8 = st.r / 8;
+    const int total_chunks = st.M * D * r8;
+    for (int idx = threadIdx.x; idx < total_chunks; idx += kEditThreads) {
+      const int m = idx / (D * r8), rm = idx % (D * r8);
+      const int d = rm / r8, v = rm % r8;
+      *reinterpret_cast<uint4*>(UN + (size_t)d * UN_LD + m * st.r + 8 * v) =
+          *reinterpret_cast<const uint4*>(Uh + ((size_t)m * D + d) * st.r + 8 * v);
+    }
+    for (int r = threadIdx.x; r < Rpad; r += kEditThreads) {
+      float c = 0.f;
+      if (r < R) c = gain * (st.w ? st.w[((size_t)b * Hkv + h) * st.M + r / st.r] : 1.f);
+      cvec[r] = c;
+    }
+  } else {
     const uint16_t* Uh = reinterpret_cast<const uint16_t*>(st.U) + (size_t)h * st.M * D * st.r;
     // A thread takes the same 8 columns of four consecutive rows d (four 16-byte pieces of U), so that the
     // transposed copy is written 8 bytes at a time instead of 2.
@@ -186,7 +210,17 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint
         for (int tg = 0; tg < TG; ++tg) acc[tg] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(UT + (size_t)(16 * rb + j) * UT_LD + 32 * s + 8 * g);
+          bf16x8 a;
+          if (WIDE) {
+            // U^T fragment (row r = 16 rb + j, k = d = 32 s + 8 g + e) out of the row-d layout: a group of 16 lanes
+            // reads 4 rows x 16 columns (lane: row d0 + j / 4, columns 16 rb + 4 (j % 4) ..) and receives them transposed
+            const uint16_t* up = UN + (size_t)(32 * s + 8 * g + (j >> 2)) * UN_LD + 16 * rb + 4 * (j & 3);
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((edit_lds_s16x4_ptr)(up));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((edit_lds_s16x4_ptr)(up + 4 * UN_LD));
+            a = __builtin_shufflevector(__builtin_bit_cast(bf16x4, lo), __builtin_bit_cast(bf16x4, hi), 0, 1, 2, 3, 4, 5, 6, 7);
+          } else {
+            a = *reinterpret_cast<const bf16x8*>(UT + (size_t)(16 * rb + j) * UT_LD + 32 * s + 8 * g);
+          }
 #pragma unroll
           for (int tg = 0; tg < TG; ++tg) acc[tg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, kreg[tg][s], acc[tg], 0, 0, 0);
         }
@@ -219,7 +253,14 @@ __global__ __launch_bounds__(kEditThreads) void edit_keys_bf16_kernel(const uint
 #pragma unroll
       for (int ks2 = 0; ks2 < MAXKS2; ++ks2) {
         if (ks2 < nks2) {
-          const bf16x8 a = *reinterpret_cast<const bf16x8*>(UN + (size_t)d_row * UN_LD + 32 * ks2 + 8 * g);
+          bf16x8 a;
+          if (WIDE) {
+            // slot e of lane (j, g) is column r = 32 ks2 + 16 (e / 4) + 4 g + e % 4: two 8-byte pieces of row d_row
+            const uint16_t* up = UN + (size_t)d_row * UN_LD + 32 * ks2 + 4 * g;
+            a = __builtin_shufflevector(*reinterpret_cast<const bf16x4*>(up), *reinterpret_cast<const bf16x4*>(up + 16), 0, 1, 2, 3, 4, 5, 6, 7);
+          } else {
+            a = *reinterpret_cast<const bf16x8*>(UN + (size_t)d_row * UN_LD + 32 * ks2 + 8 * g);
+          }
 #pragma unroll
           for (int tg = 0; tg < TG; ++tg) acc[tg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, zb[tg][ks2], acc[tg], 0, 0, 0);
         }
@@ -312,9 +353,8 @@ hipError_t launch_edit_keys(const void* K_in, void* K_out, int B, int S, int Hkv
   if (dtype == SEKA_BF16) {
     const int R = steer.M * steer.r;
     const int Rpad = (R + 31) / 32 * 32;
-    const size_t smem = ((size_t)Rpad * (D + 8) + (size_t)D * (Rpad + 8)) * 2 + (size_t)Rpad * 4;
-    // Large ranks (a 70 KB staging area: two workgroups per CU): 128-token tiles, a wave owns two groups of 16 tokens.
-    const bool wide = Rpad > 64;
+    const bool wide = Rpad > 64;          // see the kernel (at smaller ranks the two-copy form measured the same or faster): one staged copy of U, 128-token tiles
+    const size_t smem = ((wide ? 0 : (size_t)Rpad * (D + 8)) + (size_t)D * (Rpad + 8)) * 2 + (size_t)Rpad * 4;
     const int tok = wide ? 2 * kEditTokens : kEditTokens;
     const dim3 grid((S + tok - 1) / tok, Hkv, B);
     auto launch = [&](auto kernel) -> hipError_t {

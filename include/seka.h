@@ -227,7 +227,8 @@ seka_status seka_attention_prefill_packed(const void* Q, const void* K, const vo
  * seq_lens  dev [B] int32 or NULL (= S for every prompt); values are clamped to [0, S]; a prompt with no
  *           cached token gets O = 0 and lse = -inf.
  * workspace dev scratch of at least seka_decode_workspace_bytes(sh) bytes, 16-byte aligned; contents on return
- *           are unspecified; calls sharing it must be ordered by their stream.
+ *           are unspecified; calls sharing it must be ordered by their stream.  (Caches short enough to be
+ *           taken in one piece per head group, S < 1024, are one kernel that does not touch it.)
  */
 size_t seka_decode_workspace_bytes(const seka_shape* sh);
 seka_status seka_attention_decode(const void* q, const void* K, const void* V, void* O, float* lse,

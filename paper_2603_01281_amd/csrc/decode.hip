@@ -92,13 +92,35 @@ __device__ __forceinline__ void merge_state(float& m, float& l, float (&o)[N], f
   for (int i = 0; i < N; ++i) o[i] = o[i] * a1 + o2[i] * a2;
 }
 
+// What a stage-1 workgroup does with the merged state (mm, ll, oo) of output element d of query head hq: with
+// several splits it goes to the partial-state buffer for stage 2; with a single split it IS the result, and the
+// workgroup writes the output and the log-sum-exp itself (the same arithmetic as stage 2 on one split, which is
+// then not launched: short caches take one kernel instead of two).
+template <typename T, int D>
+__device__ __forceinline__ void decode_emit(float mm, float ll, float oo, int b, int hq, int d, int Hq, int splits,
+                                            int split, float* __restrict__ part, T* __restrict__ O,
+                                            float* __restrict__ lse) {
+  if (splits == 1) {
+    DecElem<T>::store(O + ((size_t)b * Hq + hq) * D + d, ll > 0.f ? oo / ll : 0.f);
+    if (lse && d == 0) lse[(size_t)b * Hq + hq] = ll > 0.f ? mm * 0.6931471805599453f + logf(ll) : -INFINITY;
+    return;
+  }
+  float* dst = part + (((size_t)b * Hq + hq) * splits + split) * (D + 2);
+  dst[d] = oo;
+  if (d == 0) {
+    dst[D] = mm;
+    dst[D + 1] = ll;
+  }
+}
+
 // partial state of one (prompt, query head, split): D unnormalised outputs, then m (base-2 exponent), then l
 // (fp32 caches: every product on the vector unit, exactness over speed)
 template <typename T, int D, int GP>
 __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(const T* __restrict__ q, const T* __restrict__ K,
                                                                      const T* __restrict__ V, const int* __restrict__ lens,
                                                                      int S, int Hq, int Hkv, float c2, int splits,
-                                                                     float* __restrict__ part) {
+                                                                     float* __restrict__ part, T* __restrict__ O,
+                                                                     float* __restrict__ lse) {
   constexpr int EPL = DecElem<T>::EPL;
   constexpr int LPR = D / EPL;            // lanes per cached row
   constexpr int KPW = 64 / LPR;           // rows per wave load
@@ -205,12 +227,7 @@ __global__ __launch_bounds__(kDecThreads) void decode_partial_kernel(const T* __
       ll += sm_ml[w][g][1] * aw;
       oo += sm_o[w][g][d] * aw;
     }
-    float* dst = part + (((size_t)b * Hq + hq0 + g) * splits + split) * (D + 2);
-    dst[d] = oo;
-    if (d == 0) {
-      dst[D] = mm;
-      dst[D + 1] = ll;
-    }
+    decode_emit<T, D>(mm, ll, oo, b, hq0 + g, d, Hq, splits, split, part, O, lse);
   }
 }
 
@@ -242,7 +259,8 @@ __global__ __launch_bounds__(kDecThreads, 2) void decode_partial_mfma_kernel(con
                                                                           const uint16_t* __restrict__ V,
                                                                           const int* __restrict__ lens, int S, int Hq,
                                                                           int Hkv, int HP, float c2, int splits,
-                                                                          float* __restrict__ part) {
+                                                                          float* __restrict__ part, uint16_t* __restrict__ O,
+                                                                          float* __restrict__ lse) {
   constexpr int BK = 32;                   // keys per block
   // LDS row strides (elements).  K rows are read back 16 bytes per lane by 16 consecutive rows: a stride of 16 bytes
   // mod 256 spreads them over all banks.  V rows come back through transposing reads, where 16 lanes take 32 bytes
@@ -406,12 +424,7 @@ __global__ __launch_bounds__(kDecThreads, 2) void decode_partial_mfma_kernel(con
       ll += sm_ml[w][g][1] * aw;
       oo += sm_all[((size_t)w * kDecMfmaMaxHeads + g) * OLD + d] * aw;
     }
-    float* dst = part + (((size_t)b * Hq + hq0 + g) * splits + split) * (D + 2);
-    dst[d] = oo;
-    if (d == 0) {
-      dst[D] = mm;
-      dst[D + 1] = ll;
-    }
+    decode_emit<uint16_t, D>(mm, ll, oo, b, hq0 + g, d, Hq, splits, split, part, O, lse);
   }
 }
 
@@ -478,8 +491,9 @@ hipError_t launch_decode_gp(const void* q, const void* K, const void* V, void* O
   const float c2 = scale * 1.4426950408889634f;
   hipLaunchKernelGGL((decode_partial_kernel<T, D, GP>), dim3(splits, Hkv * chunks, B), dim3(kDecThreads), 0, s,
                      static_cast<const T*>(q), static_cast<const T*>(K), static_cast<const T*>(V), lens, S, Hq, Hkv, c2,
-                     splits, part);
-  hipLaunchKernelGGL((decode_finish_kernel<T, D>), dim3(Hq, B), dim3(kFinThreads), 0, s, part, Hq, splits, static_cast<T*>(O), lse);
+                     splits, part, static_cast<T*>(O), lse);
+  if (splits > 1)
+    hipLaunchKernelGGL((decode_finish_kernel<T, D>), dim3(Hq, B), dim3(kFinThreads), 0, s, part, Hq, splits, static_cast<T*>(O), lse);
   return hipGetLastError();
 }
 
@@ -537,12 +551,15 @@ hipError_t launch_decode(const void* q, const void* K, const void* V, void* O, f
     const float c2 = scale * 1.4426950408889634f;
     const dim3 grid(splits, Hkv * (G / hp), B);
     const uint16_t *q16 = static_cast<const uint16_t*>(q), *K16 = static_cast<const uint16_t*>(K), *V16 = static_cast<const uint16_t*>(V);
+    uint16_t* O16 = static_cast<uint16_t*>(O);
     if (D == 128) {
-      hipLaunchKernelGGL(decode_partial_mfma_kernel<128>, grid, dim3(kDecThreads), 0, s, q16, K16, V16, lens, S, Hq, Hkv, hp, c2, splits, part);
-      hipLaunchKernelGGL((decode_finish_kernel<uint16_t, 128>), dim3(Hq, B), dim3(kFinThreads), 0, s, part, Hq, splits, static_cast<uint16_t*>(O), lse);
+      hipLaunchKernelGGL(decode_partial_mfma_kernel<128>, grid, dim3(kDecThreads), 0, s, q16, K16, V16, lens, S, Hq, Hkv, hp, c2, splits, part, O16, lse);
+      if (splits > 1)
+        hipLaunchKernelGGL((decode_finish_kernel<uint16_t, 128>), dim3(Hq, B), dim3(kFinThreads), 0, s, part, Hq, splits, O16, lse);
     } else {
-      hipLaunchKernelGGL(decode_partial_mfma_kernel<64>, grid, dim3(kDecThreads), 0, s, q16, K16, V16, lens, S, Hq, Hkv, hp, c2, splits, part);
-      hipLaunchKernelGGL((decode_finish_kernel<uint16_t, 64>), dim3(Hq, B), dim3(kFinThreads), 0, s, part, Hq, splits, static_cast<uint16_t*>(O), lse);
+      hipLaunchKernelGGL(decode_partial_mfma_kernel<64>, grid, dim3(kDecThreads), 0, s, q16, K16, V16, lens, S, Hq, Hkv, hp, c2, splits, part, O16, lse);
+      if (splits > 1)
+        hipLaunchKernelGGL((decode_finish_kernel<uint16_t, 64>), dim3(Hq, B), dim3(kFinThreads), 0, s, part, Hq, splits, O16, lse);
     }
     return hipGetLastError();
   }

@@ -194,6 +194,40 @@ def test_bf16_edit_keys_standalone(seka):
     assert torch.equal(K_io, K_out)
 
 
+@pytest.mark.parametrize("D,M,r,S", [(128, 1, 64, 700), (128, 3, 24, 333), (128, 3, 32, 1000), (128, 3, 40, 129),
+                                     (128, 4, 32, 777), (128, 2, 64, 127), (64, 3, 32, 500), (64, 2, 64, 130),
+                                     (64, 1, 40, 65), (128, 1, 8, 64)])
+def test_bf16_edit_keys_ranks(seka, D, M, r, S):
+    """Standalone edit over the rank range (one staged copy of U and 128-token tiles above rank 64, two copies and
+    64-token tiles below), ranks that are not multiples of 32, lengths that end inside a tile, per-prompt expert
+    weights of either sign, per-head gains with an unselected head, key scales; out of place and in place."""
+    import torch
+    _say(f"bf16 edit D={D} M={M} r={r} S={S}")
+    B, Hkv = 2, 3
+    inp = inputs.make_layer("edit_ranks", "bf16", B=B, S=S, Hq=Hkv, Hkv=Hkv, D=D, M=M, r=r, gain=[1.0, 0.0, -0.75],
+                            mask_recipe=("cover", 0.2, 0.4, 3), seed=7 + r)
+    dev = H.DeviceInputs(inp)
+    o = H.oracle_inputs(inp)
+    rng = np.random.default_rng(r)
+    w_np = rng.uniform(-1.0, 1.0, size=(B, Hkv, M)).astype(np.float32) if M > 1 else None
+    a_np = np.array([1.0, 1.3, 0.8], np.float32)
+    ref_K = orc.edit_keys(o["K"], o["U"], inp.gain, inp.mask, w=None if w_np is None else w_np.astype(np.float64),
+                          key_scale=a_np.astype(np.float64))
+    w = None if w_np is None else torch.from_numpy(w_np).cuda()
+    K_out = torch.zeros_like(dev.K)
+    seka.seka_edit_keys(dev.K, K_out, dev.U, dev.gain, dev.mask, w=w, key_scale=list(a_np))
+    torch.cuda.synchronize()
+    amp = float(np.abs(a_np).max() + np.abs(inp.gain).max() * (np.abs(w_np).sum(axis=2).max() if M > 1 else 1.0))
+    H.assert_edit_close_bf16(H.to_f64(K_out), ref_K, amp, f"edit rank {M * r}")
+    hl = torch.from_numpy(inp.mask != 0).cuda()
+    assert torch.equal(K_out[~hl], dev.K[~hl])                    # rows that are not highlighted: bit-identical copies
+    assert torch.equal(K_out[:, :, 1], dev.K[:, :, 1])            # the unselected head too
+    assert np.abs(H.to_f64(K_out) - o["K"]).max() > 0.1           # something was edited
+    K_io = dev.K.clone()
+    seka.seka_edit_keys(K_io, K_io, dev.U, dev.gain, dev.mask, w=w, key_scale=list(a_np))
+    assert torch.equal(K_io, K_out)
+
+
 @pytest.mark.parametrize("S", [1, 2, 31, 32, 33, 63, 64, 65, 129])
 def test_bf16_tiny_lengths(seka, S):
     _say(f"bf16 tiny S={S}")

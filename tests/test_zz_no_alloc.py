@@ -57,6 +57,56 @@ def test_decode_static_two_calls_second_smaller(seka):
     _decode_both(seka, small, dev_small, [700, 64])
 
 
+@pytest.mark.parametrize("dtype,B,S,Hq,Hkv,D,lens", [
+    ("bf16", 1, 20000, 14, 2, 128, [20000]),          # 39 splits, seven heads per workgroup
+    ("bf16", 2, 9000, 40, 2, 128, [9000, 4097]),      # two head chunks of ten heads
+    ("bf16", 2, 5000, 6, 3, 64, [4999, 0]),           # D = 64, an empty prompt
+    ("f32", 2, 2600, 4, 2, 128, [2600, 513]),         # fp32 kernel
+])
+def test_decode_static_many_splits_repeated(seka, dtype, B, S, Hq, Hkv, D, lens):
+    """Shapes with many splits, seven and ten heads per workgroup, D = 64 and the fp32 kernel: three calls in a row
+    on the library's buffer, each bit-identical to the workspace entry point (nothing in the buffer has to
+    survive or be cleared between calls)."""
+    import torch
+    print(f"decode_static repeated: {dtype} B={B} S={S} Hq={Hq} Hkv={Hkv} D={D} lens={lens}", flush=True)
+    inp = inputs.make_layer("dec_static_merge", dtype, B=B, S=S, Hq=Hq, Hkv=Hkv, D=D, M=1, r=8, gain=1.0,
+                            mask_recipe=("none",), seed=31)
+    dev = H.DeviceInputs(inp)
+    ln = np.asarray(lens, np.int32)
+    q_dev = torch.stack([dev.Q[b, max(int(ln[b]) - 1, 0)] for b in range(B)]).contiguous()
+    lens_dev = torch.from_numpy(ln).cuda()
+    code = seka.SEKA_BF16 if dtype == "bf16" else seka.SEKA_F32
+    sh = seka.seka_shape(B, S, Hq, Hkv, D, code, float(inp.scale))
+    need = seka.lib.seka_decode_workspace_bytes(ctypes.byref(sh))
+    assert need > B * Hq * (D + 2) * 4, "this case is meant to have several splits"
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def run(static):
+        O = torch.full_like(q_dev, float("nan"))
+        lse = torch.full((B, Hq), float("nan"), dtype=torch.float32, device="cuda")
+        args = [q_dev.data_ptr(), dev.K.data_ptr(), dev.V.data_ptr(), O.data_ptr(), lse.data_ptr(), lens_dev.data_ptr(),
+                ctypes.byref(sh)]
+        rc = (seka.lib.seka_attention_decode_static(*args, stream) if static
+              else seka.lib.seka_attention_decode(*args, ws.data_ptr(), need, stream))
+        assert rc == 0, seka.lib.seka_status_string(rc)
+        torch.cuda.synchronize()
+        return O, lse
+
+    O_ws, L_ws = run(False)
+    for rep in range(3):
+        O_st, L_st = run(True)
+        assert torch.equal(O_ws, O_st) and torch.equal(L_ws, L_st), f"call {rep}: static result differs from the workspace result"
+    live = ln > 0
+    q_rows = np.stack([inp.widen(inp.Q)[b, max(int(ln[b]) - 1, 0)] for b in range(B)])
+    ref_O, ref_L = orc.decode_attention(q_rows[live], inp.widen(inp.K)[live], inp.widen(inp.V)[live], ln[live], scale=inp.scale)
+    if dtype == "bf16":
+        H.assert_close_bf16(H.to_f64(O_ws)[live], ref_O, "decode O")
+        H.assert_lse_close_bf16(H.to_f64(L_ws)[live], ref_L, "decode LSE", path="decode")
+    else:
+        H.assert_close_f32(H.to_f64(O_ws)[live], ref_O, "decode O")
+
+
 def test_decode_static_rejects_what_does_not_fit(seka):
     """Partial states beyond the library's buffer are a workspace error on the host: nothing is launched."""
     import torch

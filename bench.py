@@ -217,16 +217,23 @@ def time_stress_masks(torch, seka, inputs):
 
 
 def time_query_side_bound(torch, seka, inputs):
-    """What applying the edit on the query side could save at best (paper Sec. 2, Eq. 5: q . (k + g P k) = (q + g P q) . k).
-    With Q' = Q + g P Q at hand, a key tile that lies fully inside a highlighted span needs no per-tile work; a tile
-    that a span only partly covers still needs the key-side edit (or both products and a per-key select).  The fused
-    kernel is timed on the configuration's mask and on the same mask with every fully covered 64-key tile cleared:
-    the second launch does exactly the per-tile work a query-side kernel would be left with, and nothing for Q' or
-    for switching between Q and Q', so its overhead is a lower bound on that kernel's.  (The second launch computes
-    a different function; it is a timing of the fused kernel on another mask, not a result.)"""
+    """Where the fused edit's time goes and what another placement of the edit could save at best (paper Sec. 2,
+    Eq. 5: q . (k + g P k) = (q + g P q) . k).  The fused kernel is timed against the plain one on variants of a
+    configuration's mask that touch the same 64-key tiles or a subset of them:
+      key_side                 the mask as it is (what the kernel does today);
+      query_side_lower_bound   every fully covered tile cleared: with Q' = Q + g P Q at hand such a tile needs no
+                               per-tile work, a partly covered one still needs the key-side edit (or both products and
+                               a per-key select); nothing is charged for Q' or for switching between Q and Q', so
+                               this is a lower bound on a query-side kernel;
+      one_key_per_touched_tile the same tiles touched, one highlighted key each: one wave edits one 16-key block, the
+                               other seven only synchronise: the fixed cost of an edit event;
+      all_keys_of_touched_tiles the same tiles touched, every key highlighted: four waves edit;
+      nothing                  empty mask: the steered kernel's set-up.
+    (Apart from key_side these launches compute other functions; they are timings of the fused kernel on other masks.)"""
     import numpy as np
     out = {}
-    for name, cfg, recipe in (("cfg4", 4, ("cover", 0.10, 0.10, 3)), ("cfg2_70pct_contiguous", 2, None)):
+    for name, cfg, recipe in (("cfg3_layer", 3, ("cover", 0.05, 0.20, 4)), ("cfg4", 4, ("cover", 0.10, 0.10, 3)),
+                              ("cfg2_70pct_contiguous", 2, None)):
         shp = inputs.CONFIG_SHAPES[cfg]
         B, S, Hq, Hkv, D, M, r = (shp[k] for k in ("B", "S", "Hq", "Hkv", "D", "M", "r"))
         gen = torch.Generator(device="cuda"); gen.manual_seed(44 + cfg)
@@ -241,15 +248,21 @@ def time_query_side_bound(torch, seka, inputs):
         else:
             m = inputs.span_mask(B, S, 0, recipe)[0].astype(np.uint8)
         tiles = m.reshape(B, S // 64, 64)
-        full = tiles.all(axis=2)
-        m2 = np.where(full[:, :, None], 0, tiles).reshape(B, S).astype(np.uint8)
+        full, touched = tiles.all(axis=2), tiles.any(axis=2)
+        one = np.zeros_like(tiles)
+        one[:, :, 0] = touched
+        variants = (("key_side", m),
+                    ("query_side_lower_bound", np.where(full[:, :, None], 0, tiles).reshape(B, S).astype(np.uint8)),
+                    ("one_key_per_touched_tile", one.reshape(B, S)),
+                    ("all_keys_of_touched_tiles", np.repeat(touched[:, :, None], 64, axis=2).reshape(B, S).astype(np.uint8)),
+                    ("nothing", np.zeros_like(m)))
         fl = attn_flops(B, S, Hq, D)
-        res = {"tiles": int(tiles.shape[0] * tiles.shape[1]), "tiles_touched": int(tiles.any(axis=2).sum()), "tiles_fully_covered": int(full.sum())}
-        for key, mm in (("key_side_overhead_pct", m), ("query_side_lower_bound_overhead_pct", m2)):
-            mask = torch.from_numpy(mm).cuda()
+        res = {"tiles": int(touched.size), "tiles_touched": int(touched.sum()), "tiles_fully_covered": int(full.sum())}
+        for key, mm in variants:
+            mask = torch.from_numpy(np.ascontiguousarray(mm)).cuda()
             plain, steer = paired_medians(torch, lambda: seka.seka_attention_plain(Q, K, V, O),
                                           lambda: seka.seka_attention_prefill(Q, K, V, O, U, [1.0] * Hkv, mask, w=w), fl)
-            res[key] = round(100 * (steer / plain - 1), 2)
+            res[key + "_overhead_pct"] = round(100 * (steer / plain - 1), 2)
         out[name] = res
     return out
 

@@ -65,9 +65,30 @@ def test_random_configuration(seka, case):
         ref_O, ref_L = orc.steered_attention(sl(o["Q"]), sl(o["K"]), sl(o["V"]), o["U"], inp.gain, inp.mask[b:b + 1, :n],
                                              w=None if w_np is None else w_np[b:b + 1].astype(np.float64), scale=inp.scale,
                                              key_scale=None if ks is None else ks.astype(np.float64))
-        H.assert_close_bf16(got_O[b:b + 1, :n], ref_O, f"case {case} prompt {b} O")
         amp = float(np.max((1.0 if ks is None else np.abs(ks)) + np.abs(c["gain"])))      # routing weights sum to 1
-        H.assert_lse_close_bf16(got_L[b:b + 1, :, :n], ref_L, f"case {case} prompt {b} LSE", amp=amp, n_keys=n)
+        # The fixed tolerances are stated for the benchmark's regime: an edited key grows by at most the factor
+        # sqrt(1 + (amp^2 - 1) R / D) (1.3 at configurations 2-4, 1.9 at configuration 5), and its bf16 rounding, hence
+        # the score error, grows with it.  Draws beyond a factor of 2 (full-rank subspaces with gains near 2, key
+        # scales of 1.5 on top) are held to the per-row first-order bound of that error instead.
+        grow = float(np.sqrt(1.0 + max(0.0, amp * amp - 1.0) * min(c["M"] * c["r"], c["D"]) / c["D"]))
+        if grow <= 2.0:
+            H.assert_close_bf16(got_O[b:b + 1, :n], ref_O, f"case {case} prompt {b} O")
+            H.assert_lse_close_bf16(got_L[b:b + 1, :, :n], ref_L, f"case {case} prompt {b} LSE", amp=amp, n_keys=n)
+        else:
+            ob = {"Q": sl(o["Q"]), "V": sl(o["V"])}
+            K_edit = orc.edit_keys(sl(o["K"]), o["U"], inp.gain, inp.mask[b:b + 1, :n],
+                                   w=None if w_np is None else w_np[b:b + 1].astype(np.float64),
+                                   key_scale=None if ks is None else ks.astype(np.float64))
+            bO, bL, _ = _first_order_bounds(ob, K_edit, ref_O, inp.mask[b:b + 1, :n], inp.scale, c["Hq"] // c["Hkv"])
+            dO = np.abs(got_O[b:b + 1, :n] - ref_O).max(axis=3).transpose(0, 2, 1)         # [1,Hq,n]
+            dL = np.abs(got_L[b:b + 1, :, :n] - ref_L)
+            limO = np.maximum(H.BF16_MAX, bO + 2.0 ** -8 * np.abs(ref_O).max(axis=3).transpose(0, 2, 1) + 1e-4 * float(np.abs(ob["V"]).max()))
+            limL = np.maximum(H.LSE_BOUNDS["steered"][0], bL + 1e-4)
+            print(f"[first-order bounds, key growth {grow:.2f}] case {case} prompt {b}: max |dO| {dO.max():.4g} "
+                  f"(largest ratio to its bound {np.max(dO / limO):.3g}), max |dLSE| {dL.max():.4g} ({np.max(dL / limL):.3g})", flush=True)
+            assert np.isfinite(got_O[b:b + 1, :n]).all() and np.isfinite(got_L[b:b + 1, :, :n]).all()
+            assert (dO <= limO).all(), f"case {case} prompt {b}: {(dO > limO).sum()} rows exceed their first-order bound on O"
+            assert (dL <= limL).all(), f"case {case} prompt {b}: {(dL > limL).sum()} rows exceed their first-order bound on LSE"
 
 
 def _first_order_bounds(o, K_edit, ref_O, mask, scale, G, kappa=6.0):

@@ -165,6 +165,12 @@ def time_config(torch, seka, inputs, cfg, iters=10):
     fl = attn_flops(B, S, Hq, D)
     out = {"plain_ms": round(plain, 4), "steered_ms": round(steer, 4), "steered_tflops": round(fl / steer / 1e9, 1),
            "overhead_pct": round(100 * (steer / plain - 1), 2), "tokens_per_s": round(B * S / steer * 1e3)}
+    if cfg == 2:                                            # the same shape with the spans of seeds 1 and 2
+        out["overhead_pct_mask_seeds_1_2"] = []
+        for sd in (1, 2):
+            mask_s = torch.from_numpy(inputs.span_mask(B, S, sd, recipe)[0]).cuda()
+            p_s, s_s = paired_medians(torch, run_plain, lambda: seka.seka_attention_prefill(Q, K, V, O, U, gain, mask_s, w=w), fl)
+            out["overhead_pct_mask_seeds_1_2"].append(round(100 * (s_s / p_s - 1), 2))
     if route_ms is not None:
         out.update(proj_extra)
         out["route_ms"] = round(route_ms, 4)

@@ -13,8 +13,9 @@
 //   O^T = V^T P^T : B = P^T taken straight from the S^T accumulators (the contraction order over
 //                   keys is permuted identically on the V side), A = V^T fragments fetched from the
 //                   row-major V tile with the transposing LDS read (ds_read_b64_tr_b16).
-// Key edit (STEER): after a K tile lands in LDS, a wave ballot of its mask bytes tells whether it
-//   holds highlighted tokens; if so, 16-key blocks with highlights get
+// Key edit (STEER): one 64-bit highlight word per tile (bit k = key 64 t + k is highlighted) is kept in a ring in
+//   LDS, written by one thread per tile at set-up and refilled as the tile loop advances; after a K tile with a
+//   non-zero word lands in LDS, its 16-key blocks with highlights get
 //   Z^T = U_cat^T K^T and K'^T = K^T + U_cat (c .* Z^T) on 16x16x32 MFMAs, written back to LDS as bf16.
 #pragma once
 #include "common.h"
@@ -25,9 +26,9 @@ constexpr int ATT_BK = 64;   // keys per tile
 
 __host__ __device__ constexpr int att_kld(int D) { return D + 8; }     // K tile row stride (elements)
 
-inline size_t attention_bf16_smem_bytes(int D, int vpad, bool steer, int Rpad) {
+inline size_t attention_bf16_smem_bytes(int D, int vpad, bool steer, int Rpad, int threads) {
   size_t n = ((size_t)2 * ATT_BK * att_kld(D) + 2 * (size_t)ATT_BK * (D + vpad)) * 2;
-  if (steer) n += (size_t)D * (Rpad + 8) * 2 + (size_t)Rpad * 4;
+  if (steer) n += (size_t)D * (Rpad + 8) * 2 + (size_t)Rpad * 4 + (size_t)2 * threads * 8;
   return n;
 }
 
@@ -64,6 +65,8 @@ __global__ __launch_bounds__(64 * HPW * RB, D == 64 ? 4 : 1) void attention_bf16
   uint16_t* UN = Vt + 2 * V_ELEMS;                             // [D][Rpad+8]   U_cat, row d, column r (STEER)
   const int ULD = Rpad + 8;
   float* cvec = reinterpret_cast<float*>(UN + (size_t)D * ULD);   // [Rpad]  c_r = g * w_m(r)
+  // [2 NT] ring of highlight words: bit k of entry (t mod 2 NT) = key 64 t + k is highlighted (STEER)
+  unsigned long long* hlring = reinterpret_cast<unsigned long long*>(cvec + Rpad);
 
   const uint16_t* __restrict__ Qg = static_cast<const uint16_t*>(a.Q);
   const uint16_t* __restrict__ Kg = static_cast<const uint16_t*>(a.K);
@@ -137,24 +140,26 @@ __global__ __launch_bounds__(64 * HPW * RB, D == 64 ? 4 : 1) void attention_bf16
 
   // ---- tile movement: global -> registers -> LDS (K and V separately) ----
   uint4 kpre[NCH], vpre[NCH];
-  int mpre = 0;
 
+  // A tile's rows: one base per tile that is the same for every lane (scalar registers) plus a per-lane 32-bit
+  // offset that never changes (row * Hkv * D + chunk, under 64 rows), the same for K and V.
+  const size_t head_off = (tok0 * a.Hkv + h) * D;
+  const size_t tile_stride = (size_t)BK * a.Hkv * D;
+  unsigned loff[NCH];
+#pragma unroll
+  for (int n = 0; n < NCH; ++n) {
+    const int c = tid + NT * n;
+    loff[n] = (unsigned)((c / CPR) * a.Hkv * D + 8 * (c % CPR));
+  }
   auto load_rows = [&](const uint16_t* __restrict__ src, int t, uint4 (&dst)[NCH]) {
+    const uint16_t* __restrict__ tb = src + head_off + (size_t)t * tile_stride;
 #pragma unroll
     for (int n = 0; n < NCH; ++n) {
       const int c = tid + NT * n;
-      const int row = c / CPR, cc = c % CPR;
-      const int key = t * BK + row;
+      const int key = t * BK + c / CPR;
       uint4 v = make_uint4(0, 0, 0, 0);
-      if ((NCH * NT == CHUNKS || c < CHUNKS) && key < S)
-        v = *reinterpret_cast<const uint4*>(src + ((tok0 + key) * a.Hkv + h) * D + 8 * cc);
+      if ((NCH * NT == CHUNKS || c < CHUNKS) && key < S) v = *reinterpret_cast<const uint4*>(tb + loff[n]);
       dst[n] = v;
-    }
-  };
-  auto load_mask = [&](int t) {
-    if (STEER && steer_on) {
-      const int key = t * BK + lane;
-      mpre = key < S ? st.mask[tok0 + key] : 0;
     }
   };
   auto store_rows = [&](uint16_t* dst, int ld, const uint4 (&src)[NCH]) {
@@ -167,7 +172,42 @@ __global__ __launch_bounds__(64 * HPW * RB, D == 64 ? 4 : 1) void attention_bf16
       }
     }
   };
-  auto tile_ballot = [&]() -> unsigned long long { return (STEER && steer_on) ? __ballot(mpre != 0) : 0ull; };
+  // Highlight words of the tiles [t0, t0 + NT), one thread per tile, into the ring.  Every NT-th iteration refills
+  // the half of the ring that the tile loop has left behind, so no lane carries mask state through the loop.
+  auto fill_ring = [&](int t0) {
+    const int t = t0 + tid;
+    if (t < ntiles) {
+      const uint8_t* mrow = st.mask + tok0 + (size_t)t * BK;
+      unsigned long long bits = 0ull;
+      if (t * BK + BK <= S && (reinterpret_cast<uintptr_t>(mrow) & 15) == 0) {
+        uint4 mv[BK / 16];
+#pragma unroll
+        for (int q = 0; q < BK / 16; ++q) mv[q] = reinterpret_cast<const uint4*>(mrow)[q];
+#pragma unroll
+        for (int q = 0; q < BK / 16; ++q) {
+          const uint32_t x4[4] = {mv[q].x, mv[q].y, mv[q].z, mv[q].w};
+#pragma unroll
+          for (int w = 0; w < 4; ++w) {
+            // non-zero test of the four bytes of x, gathered into four adjacent bits
+            const uint32_t x = x4[w];
+            const uint32_t y = ((x | ((x & 0x7f7f7f7fu) + 0x7f7f7f7fu)) & 0x80808080u) >> 7;
+            const uint32_t nib = ((y * 0x00204081u) >> 21) & 0xfu;
+            bits |= (unsigned long long)nib << (16 * q + 4 * w);
+          }
+        }
+      } else {
+        for (int k = 0; k < BK; ++k)
+          if (t * BK + k < S && mrow[k] != 0) bits |= 1ull << k;
+      }
+      hlring[t % (2 * NT)] = bits;
+    }
+  };
+  auto ring_word = [&](int t) -> unsigned long long {   // the same word in every lane, held in scalar registers
+    const unsigned long long v = hlring[t % (2 * NT)];
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);          // the builtin is signed:
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));  // no sign extension here
+    return ((unsigned long long)hi << 32) | lo;
+  };
 
   // Edit the highlighted 16-key blocks of the K tile at Kb (LDS); one wave per block.
   auto edit_tile = [&](uint16_t* Kb, unsigned long long bits) {
@@ -246,7 +286,7 @@ __global__ __launch_bounds__(64 * HPW * RB, D == 64 ? 4 : 1) void attention_bf16
 #pragma unroll
     for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
   float m_run = -1e30f, l_run = 0.f;
-  const float c2 = a.scale * 1.4426950408889634f;   // scores are kept unscaled; p = exp2((s - m) * c2)
+  const float c2 = a.scale * 1.4426950408889634f;   // p = exp2(s * c2 - m): m_run is in units of s * c2
 
   // S^T (64 keys x 32 rows) = K tile . Q^T
   auto qk_tile = [&](const uint16_t* Kb, f32x16& s0, f32x16& s1) {
@@ -272,44 +312,58 @@ __global__ __launch_bounds__(64 * HPW * RB, D == 64 ? 4 : 1) void attention_bf16
       }
     }
   };
-  // online softmax of one tile: scores -> packed P^T, running max / sum, rescale of O when a max moved
-  auto softmax_tile = [&](f32x16& s0, f32x16& s1, bf16x8 (&pb)[4]) {
-    float mx = fmaxf(s0[0], s1[0]);
-#pragma unroll
-    for (int r = 1; r < 16; ++r) mx = fmaxf(mx, fmaxf(s0[r], s1[r]));
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
-    const float mc = m_new * c2;
+  // Online softmax of one 32-key block: scores -> packed P^T (two operands), reference exponent / sum, rescale of O
+  // when the reference moved.  No row maximum in the common case: the probabilities are formed against the row's
+  // reference exponent as it stands and their sum over this lane's 16 keys tells whether that was safe; a sum beyond
+  // kSumLimit (or one that is not a number) means some score ran more than 2^8 ahead of the reference, and only then
+  // is the block's maximum taken, the reference raised and the probabilities formed again (a handful of times per
+  // row; the first block of a row always takes this turn, its reference starts at -1e30).  The PV product of a
+  // block is accumulated before the next block's softmax, so a raise rescales exactly what was formed before it.
+  constexpr float kSumLimit = 4096.f;          // 16 probabilities of at most 2^8
+  constexpr float kSlack = 8.f;
+  auto softmax_block = [&](const f32x16& sv, bf16x8 (&pb)[2]) {
+    float pv[16];
     float lsum = 0.f;
+    const float mneg = -m_run;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      s0[r] = __builtin_amdgcn_exp2f(s0[r] * c2 - mc);
-      s1[r] = __builtin_amdgcn_exp2f(s1[r] * c2 - mc);
-      lsum += s0[r] + s1[r];
+      pv[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], c2, mneg));
+      lsum += pv[r];
     }
-    l_run = l_run * alpha + lsum;
-    m_run = m_new;
+    if (__builtin_expect(__any(!(lsum <= kSumLimit)), 0)) {
+      float mx = sv[0];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      pb[0][e] = (__bf16)s0[e];
-      pb[1][e] = (__bf16)s0[8 + e];
-      pb[2][e] = (__bf16)s1[e];
-      pb[3][e] = (__bf16)s1[8 + e];
-    }
-    if (__any(alpha != 1.f)) {   // rare after the first few tiles
+      for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sv[r]);
+      mx = fmaxf(mx, __shfl_xor(mx, 32)) * c2;                 // the other 16 keys of this row live in lane ^ 32
+      const bool need = mx > m_run + kSlack;
+      const float m_new = need ? mx : m_run;
+      const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+      m_run = m_new;
+      lsum = 0.f;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        pv[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], c2, -m_new));
+        lsum += pv[r];
+      }
+      l_run *= alpha;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
         for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
     }
-  };
-  // O^T += V^T P^T
-  auto pv_tile = [&](const uint16_t* Vb, const bf16x8 (&pb)[4]) {
-    const int li = lane & 15, grp = lane >> 4;
-    const uint16_t* vbase = Vb + (4 * hf + (li >> 2)) * VLD + 16 * (grp & 1) + 4 * (li & 3);
+    l_run += lsum;
 #pragma unroll
-    for (int kb = 0; kb < 4; ++kb) {
+    for (int e = 0; e < 8; ++e) {
+      pb[0][e] = (__bf16)pv[e];
+      pb[1][e] = (__bf16)pv[8 + e];
+    }
+  };
+  // O^T += V^T P^T for the 32-key block `half` of the tile
+  auto pv_block = [&](const uint16_t* Vb, int half, const bf16x8 (&pb)[2]) {
+    const int li = lane & 15, grp = lane >> 4;
+    const uint16_t* vbase = Vb + (32 * half + 4 * hf + (li >> 2)) * VLD + 16 * (grp & 1) + 4 * (li & 3);
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
 #pragma unroll
       for (int db = 0; db < DB; ++db) {
         const uint16_t* p = vbase + (16 * kb) * VLD + 32 * db;
@@ -326,11 +380,11 @@ __global__ __launch_bounds__(64 * HPW * RB, D == 64 ? 4 : 1) void attention_bf16
   // ---------------- simple loop: load(t+1) | S(t), softmax(t), PV(t) | store(t+1) ----------------
   load_rows(Kg, 0, kpre);
   load_rows(Vg, 0, vpre);
-  load_mask(0);
+  if (STEER && steer_on) fill_ring(0);
   store_rows(Kt, KLD, kpre);
   store_rows(Vt, VLD, vpre);
-  hl = tile_ballot();
   __syncthreads();
+  if (STEER && steer_on) hl = ring_word(0);
   if (STEER && hl != 0ull) {
     edit_tile(Kt, hl);
     __syncthreads();
@@ -341,23 +395,27 @@ __global__ __launch_bounds__(64 * HPW * RB, D == 64 ? 4 : 1) void attention_bf16
     if (more) {
       load_rows(Kg, t + 1, kpre);
       load_rows(Vg, t + 1, vpre);
-      load_mask(t + 1);
+      if (STEER && steer_on) {
+        hl = ring_word(t + 1);                    // written at least one barrier ago
+        if (__builtin_expect(t % NT == 0, 0)) fill_ring(t + NT);       // tiles t + NT .. t + 2 NT - 1 replace t - NT .. t - 1
+      }
     }
     if (t <= tw_last) {
       f32x16 s0, s1;
-      bf16x8 pb[4];
+      bf16x8 pb[2];
       qk_tile(Kt + buf * K_ELEMS, s0, s1);
       causal_mask(t, s0, s1);
-      softmax_tile(s0, s1, pb);
-      pv_tile(Vt + buf * V_ELEMS, pb);
+      softmax_block(s0, pb);
+      pv_block(Vt + buf * V_ELEMS, 0, pb);
+      softmax_block(s1, pb);
+      pv_block(Vt + buf * V_ELEMS, 1, pb);
     }
     if (more) {
       store_rows(Kt + (buf ^ 1) * K_ELEMS, KLD, kpre);
       store_rows(Vt + (buf ^ 1) * V_ELEMS, VLD, vpre);
-      hl = tile_ballot();
     }
     __syncthreads();
-    if (STEER && more && hl != 0ull) {
+    if (STEER && more && __builtin_expect(hl != 0ull, 0)) {
       edit_tile(Kt + (buf ^ 1) * K_ELEMS, hl);
       __syncthreads();
     }
@@ -378,7 +436,7 @@ __global__ __launch_bounds__(64 * HPW * RB, D == 64 ? 4 : 1) void attention_bf16
         *reinterpret_cast<uint2*>(op + 32 * db + 8 * q4) = __builtin_bit_cast(uint2, o4);
       }
     }
-    if (a.lse && hf == 0) a.lse[lse_index(a, b, hq, tok0, qi)] = m_run * a.scale + logf(l_tot);
+    if (a.lse && hf == 0) a.lse[lse_index(a, b, hq, tok0, qi)] = m_run * 0.6931471805599453f + logf(l_tot);
   }
 }
 

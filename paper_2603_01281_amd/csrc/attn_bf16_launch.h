@@ -12,7 +12,7 @@ template <int D, int HPW, int RB, bool STEER>
 hipError_t launch_attention_bf16_cfg(const AttnArgs& a, const SteerArgs* steer, hipStream_t s) {
   constexpr int BQ = 32 * RB;
   const int Rpad = STEER ? (steer->M * steer->r + 31) / 32 * 32 : 0;
-  const size_t smem = attention_bf16_smem_bytes(D, kAttnVPad, STEER, Rpad);
+  const size_t smem = attention_bf16_smem_bytes(D, kAttnVPad, STEER, Rpad, 64 * HPW * RB);
   auto kernel = attention_bf16_kernel<D, HPW, RB, STEER, kAttnVPad>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);

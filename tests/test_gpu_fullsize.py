@@ -166,3 +166,17 @@ def test_very_long_prompt_takes_the_register_staged_kernel(seka):
     rows = H.sample_rows(inp, per_head=3, seed=5)
     _check_rows(seka, inp, dev, rows, steered=True, what="long steered")
     _check_rows(seka, inp, dev, rows, steered=False, what="long plain")
+
+
+def test_long_prompt_d64_refills_the_highlight_ring(seka):
+    """bf16 D = 64 runs on the register-staged kernel, whose highlight words live in a ring of 2 x (threads per
+    workgroup) tiles that is refilled as the tile loop advances: 70k tokens are 1094 tiles, more than the ring
+    holds for any workgroup shape, so late tiles reuse entries of early ones; sampled rows around every span."""
+    S = 70_000
+    _say(f"long prompt D=64 S={S}")
+    inp = inputs.make_layer("long64", "bf16", B=1, S=S, Hq=2, Hkv=1, D=64, M=1, r=32, gain=1.0,
+                            mask_recipe=("lengths", 12, 48, 400), seed=67)
+    dev = H.DeviceInputs(inp)
+    rows = H.sample_rows(inp, per_head=3, seed=6)
+    _check_rows(seka, inp, dev, rows, steered=True, what="long D=64 steered")
+    _check_rows(seka, inp, dev, rows, steered=False, what="long D=64 plain")

@@ -171,7 +171,9 @@ seka_status seka_edit_keys_packed(const void* K_in, void* K_out, const seka_shap
 /*
  * seka_attention_prefill — causal attention on the edited keys, edit fused in (paper Sec. 2 and
  * Eq. 5: logits_ij = q_i . k'_j / sqrt(d_k), j <= i; softmax over j; O_i = sum_j p_ij v_j).
- * K itself is not modified: edited keys exist only on chip.
+ * K itself is not modified: edited keys exist only on chip, or not at all: for bf16, D = 128,
+ * M * r <= 32 and unit key scales the same logits are formed on the score side,
+ * q_i . k_j + (U^T q_i) . (c .* U^T k_j) for highlighted j (the equivalence stated in Sec. 2).
  *
  * Q, O  dev [B,S,Hq,D];  K, V  dev [B,S,Hkv,D];  all tensor dtype.
  * lse   dev [B,Hq,S] fp32 or NULL: natural log of the softmax denominator (row maximum included).

@@ -35,7 +35,11 @@ hipError_t launch_attention_bf16_pipe_r128(const AttnArgs& a, const SteerArgs* s
 inline hipError_t launch_attention_bf16_pipe(const AttnArgs& a, const SteerArgs* steer, hipStream_t s) {
   if (!steer) return launch_attention_bf16_pipe_plain(a, s);
   const int R = steer->M * steer->r;
-  if (R <= 32) return launch_attention_bf16_pipe_r32(a, steer, s);
+  // The rank <= 32 kernel applies the edit to the scores and has no place for a key scale other than 1 (Eq. 4's
+  // negative-side gain): such calls take the dense form, which edits the keys themselves.
+  bool unit_scale = true;
+  for (int h = 0; h < a.Hkv; ++h) unit_scale = unit_scale && (steer->gain[h] == 0.f || steer->kscale[h] == 1.f);
+  if (R <= 32 && unit_scale) return launch_attention_bf16_pipe_r32(a, steer, s);
   if (R <= 64) return launch_attention_bf16_pipe_r64(a, steer, s);
   return launch_attention_bf16_pipe_r128(a, steer, s);
 }

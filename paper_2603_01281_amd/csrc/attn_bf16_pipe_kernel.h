@@ -26,8 +26,10 @@
 // The softmax runs per 32-key block (half a tile), which halves the score registers the pipeline needs.
 // K tiles live in a ring of three LDS stages; V in a ring of six half tiles that runs half a tile behind K
 // (see the tile loads).  K(t+2) and the V blocks 2t+3, 2t+4 are requested during iteration t (in the hot loop
-// between its two steps, so that the first step's LDS reads follow the per-tile barrier directly) and K(t+2) is
-// edited (highlighted keys only) between the two steps of iteration t + 1.
+// between its two steps, so that the first step's LDS reads follow the per-tile barrier directly).  The steering
+// event of tile t+2 (highlighted keys only) sits between the two steps of iteration t + 1: at rank <= 32 the
+// coordinates c .* U^T k of its keys are computed and the scores of that tile get a rank-32 correction against
+// U^T q afterwards (score-side form, the tile itself stays as loaded); at larger ranks the keys are edited in LDS.
 #pragma once
 #include <type_traits>
 
@@ -35,18 +37,26 @@
 
 namespace seka {
 
-// LDS beyond the two tile rings (steered kernels): the edit's matrix operands, the per-column coefficients and
-// one 64-bit highlight word per tile.  Rank <= 32 (nkr == 1): U_cat stored twice, once per product of the
-// low-rank edit k' = k + U_cat (c . U_cat^T k).  Larger ranks: the dense D x D matrix g P = U_cat diag(c) U_cat^T,
-// built once per workgroup; at rank >= 64 one product with it moves no more operand bytes than the two low-rank
-// products and has no intermediate.  Either way the operands are stored in the order the MFMAs read them (one
-// conflict-free 16-byte LDS read per lane and operand).
-inline size_t attention_bf16_pipe_smem_bytes(int S, bool steer, int nkr) {
+// LDS beyond the two tile rings (steered kernels): the edit's matrix operand, the per-column coefficients, one
+// 64-bit highlight word per tile and, for rank <= 32, the buffers of the score-side form.
+// Rank <= 32 (nkr == 1): the edit is applied to the scores, s_ij = q_i . k_j + (U^T q_i) . (c .* U^T k_j) for
+// highlighted j (paper Sec. 2, the equivalence of key-side and score-side control, Eq. 5): U_cat is stored once, as
+// the operand of U_cat^T K^T; the coordinates c .* U^T k of a tile's keys go to one of two 64 x 32 bf16 buffers
+// (rows padded to 80 bytes: conflict-free 16-byte row reads), and every wave keeps U^T q of its 32 rows as two
+// MFMA operands (2 KB).  Larger ranks: the keys themselves are edited with the dense D x D matrix
+// g P = U_cat diag(c) U_cat^T, built once per workgroup; at rank >= 64 one product with it moves no more operand
+// bytes than two low-rank products and has no intermediate.  Either way the operands are stored in the order the
+// MFMAs read them (one 16-byte LDS read per lane and operand).
+constexpr int PIPE_Z_LD = 80;                       // bytes per key in a coordinate buffer
+constexpr int PIPE_Z_BYTES = DMA_BK * PIPE_Z_LD;    // one buffer
+constexpr int PIPE_QT_BYTES = 2048;                 // U^T q of one wave: [2 k-slices][64 lanes][8] bf16
+inline size_t attention_bf16_pipe_smem_bytes(int S, bool steer, int nkr, int nwaves) {
   size_t n = (size_t)2 * DMA_STAGES * DMA_TILE_BYTES;
   if (steer) {
     const int Rpad = 32 * nkr;
-    n += nkr == 1 ? (size_t)2 * DMA_D * Rpad * 2 : (size_t)DMA_D * DMA_D * 2;
+    n += nkr == 1 ? (size_t)DMA_D * Rpad * 2 : (size_t)DMA_D * DMA_D * 2;
     n += (size_t)Rpad * 4;
+    if (nkr == 1) n += (size_t)2 * PIPE_Z_BYTES + (size_t)nwaves * PIPE_QT_BYTES;
     n += (size_t)((S + DMA_BK - 1) / DMA_BK) * 8;
   }
   return n;
@@ -99,10 +109,12 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   constexpr bool kEventsInHot = STEER && (!DENSE || NW == 8);   // steering events handled inside the hot loop (see the tile loop)
   uint16_t* UN = reinterpret_cast<uint16_t*>(smem + 2 * DMA_STAGES * TB);
   uint16_t* U1 = UN;                       // low rank: operand (rb, s) of U_cat^T K^T: [2][4][64 lanes][8]
-  uint16_t* U2 = UN + D * Rpad;            // low rank: operand (s, half) of U_cat Z: [4][2][64 lanes][8]
   uint16_t* AP = UN;                       // dense: operand (s_out, half, ks) of (g P) K^T: [4][2][4][64 lanes][8]
-  float* cvec = reinterpret_cast<float*>(UN + (DENSE ? (size_t)D * D : (size_t)2 * D * Rpad));   // [Rpad]
-  unsigned long long* hlbits = reinterpret_cast<unsigned long long*>(cvec + Rpad);       // [tiles] (STEER)
+  float* cvec = reinterpret_cast<float*>(UN + (DENSE ? (size_t)D * D : (size_t)D * Rpad));   // [Rpad]
+  unsigned char* zbuf = reinterpret_cast<unsigned char*>(cvec + Rpad);     // low rank: [2][64 keys][80 B] coordinates
+  unsigned char* qtbuf = zbuf + 2 * PIPE_Z_BYTES;                          // low rank: [NW][2][64 lanes][8] U^T q
+  unsigned long long* hlbits = reinterpret_cast<unsigned long long*>(      // [tiles] (STEER)
+      DENSE ? reinterpret_cast<unsigned char*>(cvec + Rpad) : qtbuf + NW * PIPE_QT_BYTES);
 
   const uint16_t* __restrict__ Qg = static_cast<const uint16_t*>(a.Q);
   const uint16_t* __restrict__ Kg = static_cast<const uint16_t*>(a.K);
@@ -335,26 +347,17 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
       } else {
         const int r0 = m * st.r + 8 * v;              // concatenated column of the first of these 8 elements
         const uint16_t* e16 = reinterpret_cast<const uint16_t*>(&val);
-        // first product: operand (rb, s), lane (g, j) holds U_cat[d = 32 s + 8 g + e][r = 16 rb + j], e = 0..7
+        // operand (rb, s) of U_cat^T K^T: lane (g, j) holds U_cat[d = 32 s + 8 g + e][r = 16 rb + j], e = 0..7
         const int s1 = d >> 5, g1 = (d >> 3) & 3, e1 = d & 7;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const int r = r0 + i;
           U1[((((r >> 4) * 4 + s1) * 64) + g1 * 16 + (r & 15)) * 8 + e1] = e16[i];
         }
-        // second product: operand (s, half), lane (g, j) holds U_cat[d = 32 s + 8 (j / 4) + 4 half + j % 4]
-        // [r = 16 (e / 4) + 4 g + e % 4], e = 0..7: four consecutive columns are four consecutive slots
-        const int dl = d & 31, j2 = 4 * (dl >> 3) + (dl & 3), half2 = (dl >> 2) & 1;
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
-          const int rl = (r0 + 4 * q) & 31;
-          uint16_t* dst = U2 + ((((s1 * 2 + half2) * 64) + ((rl & 15) >> 2) * 16 + j2) * 8 + 4 * (rl >> 4));
-          *reinterpret_cast<uint2*>(dst) = q == 0 ? make_uint2(val.x, val.y) : make_uint2(val.z, val.w);
-        }
       }
     };
     if (!DENSE && R != Rpad) {
-      for (int i = tid; i < 2 * D * Rpad / 8; i += NT) reinterpret_cast<uint4*>(UN)[i] = make_uint4(0, 0, 0, 0);
+      for (int i = tid; i < D * Rpad / 8; i += NT) reinterpret_cast<uint4*>(UN)[i] = make_uint4(0, 0, 0, 0);
       __syncthreads();
     }
 #pragma unroll
@@ -418,8 +421,9 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     return __ballot(v != 0ull);
   };
 
-  // Edit the highlighted 16-key blocks of the (swizzled) K tile at Kb: wave w < 4 owns block w.  What bounds the
-  // edit is LDS traffic for its matrix operands (every block reads all of them), so blocks are not split further.
+  // Dense form (rank > 32): edit the highlighted 16-key blocks of the (swizzled) K tile at Kb in place; wave w < 4
+  // owns block w.  What bounds the edit is LDS traffic for its matrix operand (every block reads all of it), so
+  // blocks are not split further.
   auto edit_tile = [&](unsigned char* Kb, unsigned long long bits) __attribute__((always_inline)) {
     // The lane index is re-derived behind an opaque copy so that none of the per-lane operand addresses below
     // is hoisted out of the tile loop: they would occupy registers the attention pipeline needs.
@@ -436,63 +440,69 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     for (int s = 0; s < KS2; ++s) kreg[s] = *reinterpret_cast<const bf16x8*>(krow + 16 * ((4 * s + g) ^ j));
     const float mbit = ((bits16 >> j) & 1u) ? 1.f : 0.f;
     const float ksc = 1.f + mbit * (kscale - 1.f);        // a for highlighted keys, exactly 1 otherwise
-    bf16x8 zb;
-    bf16x8 u2[DENSE ? 1 : 2 * KS2];      // low rank: all operands of the second product, requested up front so that
-    if (!DENSE) {                        // the product runs back to back instead of one LDS round trip per slice
-#pragma unroll
-      for (int i = 0; i < KS2; ++i) u2[i] = *reinterpret_cast<const bf16x8*>(U2 + (i * 64 + ln) * 8);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    if (!DENSE) {
-      // z^T = U_cat^T K^T (rows r, columns keys), scaled by the per-column coefficient and the key's mask bit
-      float zc[8];
-#pragma unroll
-      for (int half = 0; half < 2; ++half) {
-        f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};   // two chains: even and odd slices of d
-#pragma unroll
-        for (int s = 0; s < KS2; ++s) {
-          const bf16x8 ua = *reinterpret_cast<const bf16x8*>(U1 + ((half * 4 + s) * 64 + ln) * 8);
-          acc[s & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua, kreg[s], acc[s & 1], 0, 0, 0);
-        }
-        const f32x4 c4 = *reinterpret_cast<const f32x4*>(cvec + 16 * half + 4 * g);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) zc[4 * half + i] = (acc[0][i] + acc[1][i]) * (c4[i] * mbit);
-      }
-      // next B operand: slot e <-> r = 16 (e / 4) + 4 g + e % 4
-#pragma unroll
-      for (int e = 0; e < 8; ++e) zb[e] = (__bf16)zc[e];
-#pragma unroll
-      for (int i = KS2; i < 2 * KS2; ++i) u2[i] = *reinterpret_cast<const bf16x8*>(U2 + (i * 64 + ln) * 8);
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    // k' = k + U_cat z (low rank) or k + mask (g P) k (dense): output rows d are permuted so that each result
-    // lands in the lane that holds that element of k
+    // k' = a k + mask (g P) k: output rows d are permuted so that each result lands in the lane that holds that
+    // element of k
 #pragma unroll
     for (int s = 0; s < KS2; ++s) {
       float outv[8];
 #pragma unroll
       for (int half = 0; half < 2; ++half) {
-        if (!DENSE) {
-          const f32x4 acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(u2[s * 2 + half], zb, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+        f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
 #pragma unroll
-          for (int i = 0; i < 4; ++i) outv[4 * half + i] = (float)kreg[s][4 * half + i] * ksc + acc[i];
-        } else {
-          f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};
-#pragma unroll
-          for (int ks = 0; ks < KS2; ++ks) {
-            const bf16x8 ua = *reinterpret_cast<const bf16x8*>(AP + (((s * 2 + half) * 4 + ks) * 64 + ln) * 8);
-            acc[ks & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua, kreg[ks], acc[ks & 1], 0, 0, 0);
-          }
-#pragma unroll
-          for (int i = 0; i < 4; ++i)
-            outv[4 * half + i] = (float)kreg[s][4 * half + i] * ksc + mbit * (acc[0][i] + acc[1][i]);
-          __builtin_amdgcn_sched_barrier(0);     // keeps the operand reads of later row groups from piling up in registers
+        for (int ks = 0; ks < KS2; ++ks) {
+          const bf16x8 ua = *reinterpret_cast<const bf16x8*>(AP + (((s * 2 + half) * 4 + ks) * 64 + ln) * 8);
+          acc[ks & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua, kreg[ks], acc[ks & 1], 0, 0, 0);
         }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          outv[4 * half + i] = (float)kreg[s][4 * half + i] * ksc + mbit * (acc[0][i] + acc[1][i]);
+        __builtin_amdgcn_sched_barrier(0);     // keeps the operand reads of later row groups from piling up in registers
       }
       bf16x8 o;
 #pragma unroll
       for (int e = 0; e < 8; ++e) o[e] = (__bf16)outv[e];
       *reinterpret_cast<bf16x8*>(krow + 16 * ((4 * s + g) ^ j)) = o;
+    }
+  };
+
+  // Score-side form (rank <= 32): the coordinates c .* (U_cat^T k) of the 64 keys of the (swizzled, unchanged) K
+  // tile at Kb, zero for keys that are not highlighted, into the buffer at zdst; wave w < 4 owns the 16-key block w
+  // (a block without highlights only stores zeros).  A key's 32 coordinates are stored in the order the score
+  // correction contracts them: k-slice ks2, half hf, slot e  <->  r = 16 ks2 + 4 hf + 8 (e / 4) + e % 4, which is
+  // the order in which a lane of the 32 x 32 accumulator holds U^T q of its query row (see make_qt).
+  auto coords_tile = [&](const unsigned char* Kb, unsigned long long bits, unsigned char* zdst) __attribute__((always_inline)) {
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
+    const int j = ln & 15, g = ln >> 4;
+    constexpr int KS2 = D / 32;
+    const int kblk = wave;
+    if (kblk >= BK / 16) return;                          // wave-uniform
+    const unsigned bits16 = (unsigned)((bits >> (16 * kblk)) & 0xffffull);
+    // this lane's results: key 16 kblk + j, coordinates r = 16 half + 4 g + i  ->  k-slice half, hf = g & 1, slots 4 (g / 2) + i
+    unsigned char* zrow = zdst + (16 * kblk + j) * PIPE_Z_LD + 16 * (g & 1) + 8 * (g >> 1);
+    if (bits16 == 0) {
+      *reinterpret_cast<uint2*>(zrow) = make_uint2(0, 0);
+      *reinterpret_cast<uint2*>(zrow + 32) = make_uint2(0, 0);
+      return;
+    }
+    const unsigned char* krow = Kb + (16 * kblk + j) * 256;     // row & 15 == j
+    bf16x8 kreg[KS2];   // K^T as B operand: lane (col = key j, k = d = 32 s + 8 g + e) = logical chunk 4 s + g
+#pragma unroll
+    for (int s = 0; s < KS2; ++s) kreg[s] = *reinterpret_cast<const bf16x8*>(krow + 16 * ((4 * s + g) ^ j));
+    const float mbit = ((bits16 >> j) & 1u) ? 1.f : 0.f;
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      f32x4 acc[2] = {{0.f, 0.f, 0.f, 0.f}, {0.f, 0.f, 0.f, 0.f}};   // two chains: even and odd slices of d
+#pragma unroll
+      for (int s = 0; s < KS2; ++s) {
+        const bf16x8 ua = *reinterpret_cast<const bf16x8*>(U1 + ((half * 4 + s) * 64 + ln) * 8);
+        acc[s & 1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ua, kreg[s], acc[s & 1], 0, 0, 0);
+      }
+      const f32x4 c4 = *reinterpret_cast<const f32x4*>(cvec + 16 * half + 4 * g);
+      bf16x4 z4;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) z4[i] = (__bf16)((acc[0][i] + acc[1][i]) * (c4[i] * mbit));
+      *reinterpret_cast<uint2*>(zrow + 32 * half) = __builtin_bit_cast(uint2, z4);
     }
   };
 
@@ -677,7 +687,38 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     return rest != 0ull ? tile + 1 + __builtin_ctzll(rest) : (tile | 63) + 1;
   };
   int tile_evt = 0x7fffffff;
-  if (STEER) {
+  int ztile = -1;                      // score-side form: the tile whose coordinates were computed last
+  if (STEER && !DENSE) {
+    // U^T q of this wave's 32 query rows: (U_cat^T Q^T)[r][row] on the 32 x 32 MFMA, A = U_cat^T rows r = l32 taken
+    // from the operand store of U_cat^T K^T (entry (rb, s), lane (g, j) with r = 16 rb + j, d = 32 s + 8 g + e),
+    // B = the Q fragments.  A lane ends up with its query row's coordinates r = 8 (i / 4) + 4 hf + i % 4, i = 0..15:
+    // converted to bf16 they are the two B operands of the score correction as they stand, kept in LDS (each lane
+    // reads back what it wrote: no barrier).
+    if (steer_on) {
+      f32x16 qt;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) qt[r] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        const bf16x8 ua = *reinterpret_cast<const bf16x8*>(
+            U1 + ((((l32 >> 4) * 4 + (ks >> 1)) * 64) + (2 * (ks & 1) + hf) * 16 + (l32 & 15)) * 8);
+        qt = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ua, qf[0][ks], qt, 0, 0, 0);
+      }
+      bf16x8 q8[2];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { q8[0][e] = (__bf16)qt[e]; q8[1][e] = (__bf16)qt[8 + e]; }
+      unsigned char* qp = qtbuf + wave * PIPE_QT_BYTES + lane * 16;
+      *reinterpret_cast<bf16x8*>(qp) = q8[0];
+      *reinterpret_cast<bf16x8*>(qp + PIPE_QT_BYTES / 2) = q8[1];
+    }
+    anyw = any_word(0);
+    if (anyw & 1ull) {
+      coords_tile(Kst, hlbits[0], zbuf);
+      dma_barrier();
+      ztile = 0;
+    }
+    tile_evt = next_event(0);          // tile 1 is handled by iteration 0 like every later tile
+  } else if (STEER) {
     anyw = any_word(0);
     if (anyw & 3ull) {
       if (anyw & 1ull) edit_tile(Kst, hlbits[0]);
@@ -686,6 +727,18 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     }
     tile_evt = next_event(1);
   }
+  // Score correction of one 32-key block of S^T (keys keyoff .. keyoff + 31 of `tile`): += Z (32 keys x 32 r) . (U^T q)^T,
+  // two MFMAs; A = the keys' coordinates from the tile's buffer, B = this wave's U^T q operands.
+  auto corr = [&](int tile, int keyoff, f32x16 (&sv)[RPW]) __attribute__((always_inline)) {
+    const unsigned char* zp = zbuf + (tile & 1) * PIPE_Z_BYTES + (keyoff + l32) * PIPE_Z_LD + 16 * hf;
+    const unsigned char* qp = qtbuf + wave * PIPE_QT_BYTES + lane * 16;
+#pragma unroll
+    for (int k2 = 0; k2 < 2; ++k2) {
+      const bf16x8 za = *reinterpret_cast<const bf16x8*>(zp + 32 * k2);
+      const bf16x8 qb = *reinterpret_cast<const bf16x8*>(qp + (PIPE_QT_BYTES / 2) * k2);
+      sv[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(za, qb, sv[0], 0, 0, 0);
+    }
+  };
 
   bf16x8 pb[RPW][2];           // probabilities (P^T operand) of the block whose PV product is next; none at first
 #pragma unroll
@@ -700,6 +753,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   bf16x8 kpre[2];              // first two K fragments of the block the next step scores (see `step`)
   if (0 <= tw_last) {
     qk_part(IC0{}, ICK{}, 0, sc0);
+    if (STEER && !DENSE && ztile == 0) corr(0, 0, sc0);
 #pragma unroll
     for (int rp = 0; rp < RPW; ++rp) pipe_mfma_result_guard(sc0[rp]);
   }
@@ -732,7 +786,10 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   // handled between the two steps of an iteration, where a basic-block boundary exists anyway (the conditional
   // rescale).  Directly after the per-tile barrier the same branch kept the compiler from moving the next step's
   // first LDS reads up, which cost every iteration of the steered kernels 7-9 % even with nothing to edit.  The
-  // second step is the first reader of that tile; its two prefetched fragments are read again after an edit.
+  // second step is the first reader of that tile; after an edit in place (dense form) its two prefetched
+  // fragments are read again.  In the score-side form the tile is not changed: the event leaves the tile's
+  // coordinates in the buffer of its parity (the other buffer may still be read for the previous tile's second
+  // block by waves that have not reached this event's barrier) and ztile tells the steps which scores to correct.
   auto events = [&](int t, int knext_off, bf16x8 (&kp)[2]) __attribute__((always_inline)) {
     if (!STEER) return;
     // one scalar compare in the common case; tiles past the end and unsteered heads have no bit set
@@ -742,10 +799,16 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
       if (sh == 0u) anyw = any_word(tn);
       tile_evt = next_event(tn);
       if ((anyw >> sh) & 1ull) {
-        edit_tile(Kst + (tn % 3) * TB, hlbits[tn]);
-        dma_barrier();
+        if (!DENSE) {                    // score-side: the tile stays as it is, its coordinates go to a buffer
+          coords_tile(Kst + (tn % 3) * TB, hlbits[tn], zbuf + (tn & 1) * PIPE_Z_BYTES);
+          dma_barrier();
+          ztile = tn;
+        } else {
+          edit_tile(Kst + (tn % 3) * TB, hlbits[tn]);
+          dma_barrier();
 #pragma unroll
-        for (int i = 0; i < 2; ++i) kp[i] = *(pipe_lds_bf16x8_ptr)(uintptr_t)(kaddr[i] + knext_off);
+          for (int i = 0; i < 2; ++i) kp[i] = *(pipe_lds_bf16x8_ptr)(uintptr_t)(kaddr[i] + knext_off);
+        }
       }
     }
   };
@@ -838,9 +901,11 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 #pragma unroll
     for (int db = 0; db < DB; ++db) asm volatile("" : "+v"(vaddr[db]));
     step(integral_constant<int, ST * TB + HB>{}, integral_constant<int, ((ST + 1) % 3) * TB>{}, integral_constant<int, ((2 * ST + 5) % 6) * HB>{}, sc0, sc1, pb, kpre);
+    if (STEER && !DENSE && __builtin_expect(ztile == t, 0)) corr(t, 32, sc1);
     top(std::true_type{}, st_c, t);
     if (kEventsInHot) events(t, ((ST + 1) % 3) * TB, kpre);
     step(integral_constant<int, ((ST + 1) % 3) * TB>{}, integral_constant<int, ((ST + 1) % 3) * TB + HB>{}, integral_constant<int, 2 * ST * HB>{}, sc1, sc0, pb, kpre);
+    if (STEER && !DENSE && __builtin_expect(ztile == t + 1, 0)) corr(t + 1, 0, sc0);
     bottom(std::true_type{}, t);
   };
 
@@ -868,8 +933,10 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     top(std::false_type{}, IC0{}, t);
     const int off = (t % 3) * TB, offn = ((t + 1) % 3) * TB;
     step(off + HB, offn, (int)vpos(2 * t - 1), sc0, sc1, pb, kpre);
+    if (STEER && !DENSE && ztile == t) corr(t, 32, sc1);
     events(t, offn, kpre);
     step(offn, offn + HB, (int)vpos(2 * t), sc1, sc0, pb, kpre);
+    if (STEER && !DENSE && ztile == t + 1) corr(t + 1, 0, sc0);
     bottom(std::false_type{}, t);
     ++t;
   }
@@ -879,8 +946,10 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     top(std::false_type{}, IC0{}, t);
     const int off = (t % 3) * TB, offn = ((t + 1) % 3) * TB;
     step(off + HB, offn, (int)vpos(2 * t - 1), sc0, sc1, pb, kpre);
+    if (STEER && !DENSE && ztile == t) corr(t, 32, sc1);
     events(t, offn, kpre);
     step(offn, offn + HB, (int)vpos(2 * t), sc1, sc0, pb, kpre);
+    if (STEER && !DENSE && ztile == t + 1) corr(t + 1, 0, sc0);
     bottom(std::false_type{}, t);
   }
   // ---- the wave's last tile (causal mask, nothing further to score), then idle turns while other waves finish.
@@ -891,6 +960,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
 #pragma nounroll
   for (; t < ntiles; ++t) {
     top(std::false_type{}, IC0{}, t);
+    const bool zt = STEER && !DENSE && ztile == t;     // before the event of tile t + 1 moves ztile on
     events(t, 0, kpre);                     // this wave scores nothing further; other waves may (kpre is dead here)
     if (owed) {
       pv_half(owed_off, pb);
@@ -899,6 +969,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     if (t == tw_last) {
       const int off = (t % 3) * TB;
       qk_part(IC0{}, ICK{}, off + HB, sc1);
+      if (zt) corr(t, 32, sc1);
       if (t > 0) pv_half((int)vpos(2 * t - 1), pb);      // the block before this tile (its softmax ran in the last step)
 #pragma unroll
       for (int rp = 0; rp < RPW; ++rp) {

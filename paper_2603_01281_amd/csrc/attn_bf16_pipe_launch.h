@@ -10,7 +10,7 @@ namespace seka {
 template <int HPW, int RBW, bool STEER, int NKR>
 hipError_t launch_attention_bf16_pipe_cfg(const AttnArgs& a, const SteerArgs* steer, hipStream_t s) {
   constexpr int BQ = 32 * RBW;
-  const size_t smem = attention_bf16_pipe_smem_bytes(a.S, STEER, NKR);
+  const size_t smem = attention_bf16_pipe_smem_bytes(a.S, STEER, NKR, HPW * RBW);
   if (smem > 160 * 1024) return hipErrorNotSupported;
   auto kernel = attention_bf16_pipe_kernel<HPW, RBW, 1, STEER, NKR>;
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel),

@@ -753,7 +753,6 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   bf16x8 kpre[2];              // first two K fragments of the block the next step scores (see `step`)
   if (0 <= tw_last) {
     qk_part(IC0{}, ICK{}, 0, sc0);
-    if (STEER && !DENSE && ztile == 0) corr(0, 0, sc0);
 #pragma unroll
     for (int rp = 0; rp < RPW; ++rp) pipe_mfma_result_guard(sc0[rp]);
   }
@@ -789,7 +788,9 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   // second step is the first reader of that tile; after an edit in place (dense form) its two prefetched
   // fragments are read again.  In the score-side form the tile is not changed: the event leaves the tile's
   // coordinates in the buffer of its parity (the other buffer may still be read for the previous tile's second
-  // block by waves that have not reached this event's barrier) and ztile tells the steps which scores to correct.
+  // block) and ztile tells the next iteration which scores to correct.  No barrier of its own: the coordinates are
+  // first read after the barrier at the bottom of the iteration, by the corrections of the two score blocks of
+  // that tile at the top of the next iteration and after its first step.
   auto events = [&](int t, int knext_off, bf16x8 (&kp)[2]) __attribute__((always_inline)) {
     if (!STEER) return;
     // one scalar compare in the common case; tiles past the end and unsteered heads have no bit set
@@ -801,8 +802,7 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
       if ((anyw >> sh) & 1ull) {
         if (!DENSE) {                    // score-side: the tile stays as it is, its coordinates go to a buffer
           coords_tile(Kst + (tn % 3) * TB, hlbits[tn], zbuf + (tn & 1) * PIPE_Z_BYTES);
-          dma_barrier();
-          ztile = tn;
+          ztile = tn;                    // first read after the barrier at the bottom of this iteration
         } else {
           edit_tile(Kst + (tn % 3) * TB, hlbits[tn]);
           dma_barrier();
@@ -900,12 +900,12 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(kaddr[ks]));
 #pragma unroll
     for (int db = 0; db < DB; ++db) asm volatile("" : "+v"(vaddr[db]));
+    if (STEER && !DENSE && __builtin_expect(ztile == t, 0)) corr(t, 0, sc0);
     step(integral_constant<int, ST * TB + HB>{}, integral_constant<int, ((ST + 1) % 3) * TB>{}, integral_constant<int, ((2 * ST + 5) % 6) * HB>{}, sc0, sc1, pb, kpre);
     if (STEER && !DENSE && __builtin_expect(ztile == t, 0)) corr(t, 32, sc1);
     top(std::true_type{}, st_c, t);
     if (kEventsInHot) events(t, ((ST + 1) % 3) * TB, kpre);
     step(integral_constant<int, ((ST + 1) % 3) * TB>{}, integral_constant<int, ((ST + 1) % 3) * TB + HB>{}, integral_constant<int, 2 * ST * HB>{}, sc1, sc0, pb, kpre);
-    if (STEER && !DENSE && __builtin_expect(ztile == t + 1, 0)) corr(t + 1, 0, sc0);
     bottom(std::true_type{}, t);
   };
 
@@ -932,11 +932,11 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     }
     top(std::false_type{}, IC0{}, t);
     const int off = (t % 3) * TB, offn = ((t + 1) % 3) * TB;
+    if (STEER && !DENSE && ztile == t) corr(t, 0, sc0);
     step(off + HB, offn, (int)vpos(2 * t - 1), sc0, sc1, pb, kpre);
     if (STEER && !DENSE && ztile == t) corr(t, 32, sc1);
     events(t, offn, kpre);
     step(offn, offn + HB, (int)vpos(2 * t), sc1, sc0, pb, kpre);
-    if (STEER && !DENSE && ztile == t + 1) corr(t + 1, 0, sc0);
     bottom(std::false_type{}, t);
     ++t;
   }
@@ -945,11 +945,11 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
   for (; t < tw_last; ++t) {
     top(std::false_type{}, IC0{}, t);
     const int off = (t % 3) * TB, offn = ((t + 1) % 3) * TB;
+    if (STEER && !DENSE && ztile == t) corr(t, 0, sc0);
     step(off + HB, offn, (int)vpos(2 * t - 1), sc0, sc1, pb, kpre);
     if (STEER && !DENSE && ztile == t) corr(t, 32, sc1);
     events(t, offn, kpre);
     step(offn, offn + HB, (int)vpos(2 * t), sc1, sc0, pb, kpre);
-    if (STEER && !DENSE && ztile == t + 1) corr(t + 1, 0, sc0);
     bottom(std::false_type{}, t);
   }
   // ---- the wave's last tile (causal mask, nothing further to score), then idle turns while other waves finish.
@@ -969,7 +969,10 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     if (t == tw_last) {
       const int off = (t % 3) * TB;
       qk_part(IC0{}, ICK{}, off + HB, sc1);
-      if (zt) corr(t, 32, sc1);
+      if (zt) {
+        corr(t, 0, sc0);
+        corr(t, 32, sc1);
+      }
       if (t > 0) pv_half((int)vpos(2 * t - 1), pb);      // the block before this tile (its softmax ran in the last step)
 #pragma unroll
       for (int rp = 0; rp < RPW; ++rp) {

@@ -226,16 +226,16 @@ def time_query_side_bound(torch, seka, inputs):
     """Where the fused edit's time goes and what another placement of the edit could save at best (paper Sec. 2,
     Eq. 5: q . (k + g P k) = (q + g P q) . k).  The fused kernel is timed against the plain one on variants of a
     configuration's mask that touch the same 64-key tiles or a subset of them:
-      key_side                 the mask as it is (what the kernel does today);
+      fused                    the mask as it is (what the kernel does today: score-side form at rank <= 32, key-side dense form above);
       query_side_lower_bound   every fully covered tile cleared: with Q' = Q + g P Q at hand such a tile needs no
                                per-tile work, a partly covered one still needs the key-side edit (or both products and
                                a per-key select); nothing is charged for Q' or for switching between Q and Q', so
                                this is a lower bound on a query-side kernel;
-      one_key_per_touched_tile the same tiles touched, one highlighted key each: one wave edits one 16-key block, the
-                               other seven only synchronise: the fixed cost of an edit event;
-      all_keys_of_touched_tiles the same tiles touched, every key highlighted: four waves edit;
+      one_key_per_touched_tile the same tiles touched, one highlighted key each: one wave has a 16-key block to work
+                               on (the others synchronise, or add their score corrections): an event's fixed cost;
+      all_keys_of_touched_tiles the same tiles touched, every key highlighted: four waves have a block each;
       nothing                  empty mask: the steered kernel's set-up.
-    (Apart from key_side these launches compute other functions; they are timings of the fused kernel on other masks.)"""
+    (Apart from `fused` these launches compute other functions; they are timings of the fused kernel on other masks.)"""
     import numpy as np
     out = {}
     for name, cfg, recipe in (("cfg3_layer", 3, ("cover", 0.05, 0.20, 4)), ("cfg4", 4, ("cover", 0.10, 0.10, 3)),
@@ -257,7 +257,7 @@ def time_query_side_bound(torch, seka, inputs):
         full, touched = tiles.all(axis=2), tiles.any(axis=2)
         one = np.zeros_like(tiles)
         one[:, :, 0] = touched
-        variants = (("key_side", m),
+        variants = (("fused", m),
                     ("query_side_lower_bound", np.where(full[:, :, None], 0, tiles).reshape(B, S).astype(np.uint8)),
                     ("one_key_per_touched_tile", one.reshape(B, S)),
                     ("all_keys_of_touched_tiles", np.repeat(touched[:, :, None], 64, axis=2).reshape(B, S).astype(np.uint8)),

@@ -287,3 +287,51 @@ def test_runs_on_a_side_stream_and_is_deterministic(seka):
         s.synchronize()
         outs.append(O)
     assert torch.equal(outs[0], outs[1])
+
+
+# ------------------------------------------------------------------ where the highlighted tiles sit (bf16, D = 128, rank <= 32)
+
+_EVENT_MASKS = {
+    # name: list of (first token, length) at S = 4300 = 67 tiles of 64 keys + 12 keys
+    "first_tile_only": [(3, 40)],
+    "second_tile_only": [(64 + 17, 30)],
+    "one_key": [(64 * 5 + 31, 1)],
+    "four_consecutive_tiles": [(64 * 2 + 50, 64 * 3 + 20)],
+    "every_other_tile": [(64 * t + 10, 20) for t in range(6, 30, 2)],
+    "last_partial_tile": [(64 * 67 + 2, 9)],
+    "around_tile_64": [(64 * 63 + 60, 10), (64 * 65 + 1, 3)],
+    "block_edges": [(64 * 9 + 15, 2), (64 * 10 + 31, 2), (64 * 11 + 47, 2), (64 * 12 + 63, 2)],
+    "everything": [(0, 4300)],
+}
+
+
+_EVENT_PLAIN = {}
+
+
+@pytest.mark.parametrize("name", list(_EVENT_MASKS))
+def test_bf16_highlight_positions(seka, name):
+    """The fused kernel's steering events by position: the first tiles (handled at set-up), runs of touched tiles
+    (the two coordinate buffers alternate), single keys, keys at the edges of the 16- and 32-key blocks, the ragged
+    last tile and both sides of tile 64 (where the summary word of highlighted tiles is reloaded).  Full compare."""
+    S = 4300
+    inp = inputs.make_layer("events", "bf16", B=1, S=S, Hq=4, Hkv=1, D=128, M=1, r=32, gain=1.25,
+                            mask_recipe=("none",), seed=77)
+    for s0, n in _EVENT_MASKS[name]:
+        inp.mask[0, s0:s0 + n] = 1
+    _say(f"highlight positions {name}: {int(inp.mask.sum())} keys")
+    dev = H.DeviceInputs(inp)
+    o = H.oracle_inputs(inp)
+    ref_O, ref_L = orc.steered_attention(o["Q"], o["K"], o["V"], o["U"], inp.gain, inp.mask, scale=inp.scale)
+    got_O, got_L = _run_attention(seka, dev, True)
+    H.assert_close_bf16(got_O, ref_O, f"{name} O")
+    H.assert_lse_close_bf16(got_L, ref_L, f"{name} LSE", path="steered")
+    # the steering is visible at this size, and the error on the rows it reaches is well below what it changes
+    # (otherwise the compare would not see a missed event)
+    if "O" not in _EVENT_PLAIN:                       # the same Q, K, V in every case
+        _EVENT_PLAIN["O"] = orc.causal_attention(o["Q"], o["K"], o["V"], scale=inp.scale)[0]
+    plain_O = _EVENT_PLAIN["O"]
+    first = int(np.nonzero(inp.mask[0])[0][0])
+    effect = np.abs(ref_O[0, first:] - plain_O[0, first:]).max()
+    err = np.abs(got_O[0, first:] - ref_O[0, first:]).max()
+    print(f"{name}: steering moves the affected rows by up to {effect:.4g}, error there {err:.4g}", flush=True)
+    assert effect > 0.005 and err < 0.6 * effect

@@ -896,11 +896,11 @@ __global__ __launch_bounds__(64 * HPW * RBW) void attention_bf16_pipe_kernel(Att
     using std::integral_constant;
     // The operand addresses pass through an opaque copy once per tile: otherwise every "address + stage offset"
     // below is hoisted out of the loop into a register of its own (dozens), instead of being an immediate.
+    if (STEER && !DENSE && __builtin_expect(ztile == t, 0)) corr(t, 0, sc0);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(kaddr[ks]));
 #pragma unroll
     for (int db = 0; db < DB; ++db) asm volatile("" : "+v"(vaddr[db]));
-    if (STEER && !DENSE && __builtin_expect(ztile == t, 0)) corr(t, 0, sc0);
     step(integral_constant<int, ST * TB + HB>{}, integral_constant<int, ((ST + 1) % 3) * TB>{}, integral_constant<int, ((2 * ST + 5) % 6) * HB>{}, sc0, sc1, pb, kpre);
     if (STEER && !DENSE && __builtin_expect(ztile == t, 0)) corr(t, 32, sc1);
     top(std::true_type{}, st_c, t);
